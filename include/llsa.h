@@ -1,0 +1,144 @@
+/*
+ * llsa.h - C ABI of the MI355X (gfx950) Log-linear Sparse Attention library.
+ *
+ * One attention layer, forward and backward, as defined by Alg. 1 of the paper
+ * ("Log-linear Sparse Attention"): hierarchical compression, hierarchical
+ * Top-K selection, attention with Hierarchical KV Enrichment and KV
+ * Reweighting; backward through the selection lists (Sec. 4.3, Alg. 2).
+ *
+ * Conventions for every entry point
+ *   - Pointers named Q, K, V, O, dO, dQ, dK, dV, LSE, indices, workspace and
+ *     every pointer of the step-wise calls are DEVICE pointers owned by the
+ *     caller; `const llsa_desc*`, the plan and all `out` pointers of the query
+ *     functions are HOST pointers.
+ *   - Tensors are [batch, heads, N, d], contiguous, d innermost, element type
+ *     `desc.dtype` (fp32, or bf16 stored as 16-bit words).
+ *   - The library allocates no device memory, never synchronises the host and
+ *     only enqueues work on the given HIP stream (`hip_stream` is a
+ *     hipStream_t passed as void*; NULL = the default stream).
+ *   - All validation happens on the host before anything is enqueued: on any
+ *     status other than LLSA_OK no kernel has been launched and no output has
+ *     been touched (LLSA_ERR_RUNTIME excepted: a launch itself failed).
+ *   - Indices are 0-based.  Level l has n_l = N / B^l tokens (l = 0..L);
+ *     I^(l) (l = 0..L-1) has n_{l+1} rows of K_l = min(K, n_{l+1}) key-block
+ *     ids at level l, each row sorted ascending.
+ */
+#ifndef LLSA_H
+#define LLSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LLSA_OK = 0,
+    LLSA_ERR_NULL = 1,        /* a required pointer is NULL                              */
+    LLSA_ERR_BAD_SHAPE = 2,   /* N not divisible by B^L, L < 1, Le outside 0..L, K < 1...*/
+    LLSA_ERR_UNSUPPORTED = 3, /* a (d, B, K, dtype, size) combination no kernel handles  */
+    LLSA_ERR_WORKSPACE = 4,   /* reserved                                                */
+    LLSA_ERR_RUNTIME = 5      /* a HIP launch failed                                     */
+} llsa_status;
+
+typedef enum { LLSA_F32 = 0, LLSA_BF16 = 1 } llsa_dtype;
+
+/* Problem statement of Alg. 1 (its Input line) plus the knobs the paper leaves open. */
+typedef struct {
+    int32_t batch, heads;
+    int64_t N;          /* tokens per head; must be divisible by B^L                       */
+    int32_t d;          /* head dimension: 16, 32, 64 or 128                                */
+    int32_t B;          /* block size (2..64)                                               */
+    int32_t K;          /* Top-K parameter, same at every level (Sec. 4.1)                  */
+    int32_t L;          /* number of coarse levels (>= 1)                                   */
+    int32_t Le;         /* KV-enrichment levels, 0..L; Le = L is the paper's default        */
+    float sm_scale;     /* logits = sm_scale * q.k (+ l ln B); <= 0 selects 1/sqrt(d)       */
+    int32_t dtype;      /* llsa_dtype of Q, K, V, O and the gradients                       */
+    int32_t reweight;   /* 1: a level-l token weighs B^l (KV Reweighting); 0: weight 1      */
+    int32_t bwd_repool; /* 1: llsa_backward rebuilds the pooled K/V levels from K, V, so the
+                           workspace need not survive between the two calls; 0: backward is
+                           given the very workspace llsa_forward filled                     */
+    int32_t kernel_path;/* 0: fastest kernels available for the shape; 1: force the portable
+                           scalar kernels (any supported shape, used as a cross-check)      */
+} llsa_desc;
+
+typedef struct llsa_plan_s llsa_plan_t; /* opaque, host-only, immutable after creation */
+
+/* Validate a problem and precompute its level table and buffer layout (host only). */
+llsa_status llsa_plan(const llsa_desc *desc, llsa_plan_t **out);
+void llsa_plan_destroy(llsa_plan_t *plan);
+
+/* Bytes of device workspace llsa_forward (for_backward = 0) / llsa_backward (1) need.
+   The backward workspace starts with the forward one (same offsets). */
+size_t llsa_plan_workspace_bytes(const llsa_plan_t *plan, int for_backward);
+
+/* Total bytes of the int32 `indices` buffer: I^(0) | I^(1) | ... | I^(L-1), level l
+   stored as [batch, heads, n_{l+1}, K_l]. */
+size_t llsa_plan_indices_bytes(const llsa_plan_t *plan);
+
+/* Level l (0..L-1) of `indices`: rows per head, K_l, byte offset.  Returns L, or -1 on bad input. */
+int32_t llsa_plan_level_info(const llsa_plan_t *plan, int32_t l, int64_t *rows, int32_t *K_l,
+                             size_t *byte_offset);
+
+/* Where pooled level l (1..L) of tensor t (0 = Q, 1 = K, 2 = V) lives in the workspace:
+   [batch, heads, n_l, d] of desc.dtype.  Returns 0, or -1 on bad input. */
+int32_t llsa_plan_pyramid_info(const llsa_plan_t *plan, int32_t tensor, int32_t l, int64_t *tokens,
+                               size_t *byte_offset);
+
+/* Key-major lists of level l (0..L-1) inside the backward workspace (Alg. 2's outputs):
+   C: [batch*heads, n_{l+1} + 1] int32 offsets; Iq: [batch*heads, n_{l+1} * K_l] int32 query-block
+   rows, ascending within a key.  Returns 0, or -1 on bad input. */
+int32_t llsa_plan_csc_info(const llsa_plan_t *plan, int32_t l, size_t *C_byte_offset, size_t *Iq_byte_offset);
+
+/*
+ * Forward pass (Alg. 1 in full).
+ *   Q, K, V   in : [batch, heads, N, d]
+ *   O        out : [batch, heads, N, d]
+ *   LSE      out : [batch, heads, N] fp32, natural-log logsumexp of the logits
+ *                  (sm_scale and the l ln B weights included)
+ *   indices  out : see llsa_plan_indices_bytes
+ *   workspace    : >= llsa_plan_workspace_bytes(plan, 0); holds the pooled levels afterwards
+ */
+llsa_status llsa_forward(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O,
+                         float *LSE, int32_t *indices, void *workspace, void *hip_stream);
+
+/*
+ * Backward pass with the selection held fixed (Sec. 4.3): recomputes P from LSE and the
+ * lists, key/value gradients through the transposed lists (Alg. 2) and through the pooled
+ * coarse tokens (adjoint of the compression loop of Alg. 1).
+ *   Q, K, V, O, LSE, indices in : as given to / produced by llsa_forward
+ *   dO                       in : [batch, heads, N, d]
+ *   dQ, dK, dV              out : [batch, heads, N, d]
+ *   workspace                   : >= llsa_plan_workspace_bytes(plan, 1); see desc.bwd_repool
+ */
+llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, const void *O,
+                          const float *LSE, const int32_t *indices, const void *dO, void *dQ, void *dK,
+                          void *dV, void *workspace, void *hip_stream);
+
+/* ---- the steps of the path one by one (same kernels; used for step-wise parity checks) ---- */
+
+/* Hierarchical compression (Alg. 1, first loop): fills the pooled levels 1..L of Q, K, V in `workspace`. */
+llsa_status llsa_pool(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *workspace,
+                      void *hip_stream);
+
+/* One level of hierarchical Top-K selection (Alg. 1, second loop) at level l (1..L), reading the
+   pooled Q^(l), K^(l) from `workspace`.  parent = I^(l) [batch, heads, n_{l+1}, K_l] (ignored, may be
+   NULL, when l = L); out = I^(l-1) [batch, heads, n_l, K_{l-1}]. */
+llsa_status llsa_select_level(const llsa_plan_t *plan, int32_t l, const void *workspace, const int32_t *parent,
+                              int32_t *out, void *hip_stream);
+
+/* Attention over the gathered lists only (Alg. 1, third loop; Eq. 1-5), given pooled levels in
+   `workspace` and `indices`. */
+llsa_status llsa_attention(const llsa_plan_t *plan, const void *Q, const void *K, const void *V,
+                           const int32_t *indices, const void *workspace, void *O, float *LSE, void *hip_stream);
+
+/* Alg. 2 for every level: builds the key-major lists inside the backward workspace. */
+llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices, void *workspace, void *hip_stream);
+
+const char *llsa_status_string(llsa_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LLSA_H */

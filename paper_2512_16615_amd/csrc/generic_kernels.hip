@@ -1,0 +1,579 @@
+// Portable scalar (VALU) kernels for every step of the LLSA layer, any supported shape and both I/O
+// types.  The pooling, selection, index-transpose, D = rowsum(dO*O) and un-pooling kernels here are the
+// ones every configuration uses; the attention / dQ / dK,dV kernels here are the fallback (and the fp32
+// path), the bf16 B=16 shapes normally run the MFMA kernels instead.
+#include "llsa_internal.h"
+
+#include <math.h>
+
+namespace llsa {
+
+// ------------------------------------------------------------------------------------------ element types
+struct bf16_t { uint16_t v; };
+
+__device__ __forceinline__ float to_f(float x) { return x; }
+__device__ __forceinline__ float to_f(bf16_t x) { return __uint_as_float(((uint32_t)x.v) << 16); }
+
+template <class T> __device__ __forceinline__ T from_f(float f);
+template <> __device__ __forceinline__ float from_f<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float f) {
+    // round to nearest even; inf / nan pass through unchanged in their upper half
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7f800000u) != 0x7f800000u) u += 0x7fffu + ((u >> 16) & 1u);
+    bf16_t r; r.v = (uint16_t)(u >> 16);
+    return r;
+}
+
+template <class T> struct Vec;                       // 16-byte vector of T
+template <> struct Vec<float>  { static constexpr int n = 4; };
+template <> struct Vec<bf16_t> { static constexpr int n = 8; };
+
+template <class T> __device__ __forceinline__ void load_vec(const T *p, float *out);
+template <> __device__ __forceinline__ void load_vec<float>(const float *p, float *out) {
+    float4 v = *reinterpret_cast<const float4 *>(p);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
+template <> __device__ __forceinline__ void load_vec<bf16_t>(const bf16_t *p, float *out) {
+    uint4 v = *reinterpret_cast<const uint4 *>(p);
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        out[2 * i] = __uint_as_float(w[i] << 16);
+        out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+template <class T> __device__ __forceinline__ void store_vec(T *p, const float *in);
+template <> __device__ __forceinline__ void store_vec<float>(float *p, const float *in) {
+    *reinterpret_cast<float4 *>(p) = make_float4(in[0], in[1], in[2], in[3]);
+}
+template <> __device__ __forceinline__ void store_vec<bf16_t>(bf16_t *p, const float *in) {
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        w[i] = (uint32_t)from_f<bf16_t>(in[2 * i]).v | ((uint32_t)from_f<bf16_t>(in[2 * i + 1]).v << 16);
+    *reinterpret_cast<uint4 *>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// plain fp32 dot of a row in global memory with a vector held in LDS (fp32)
+template <class T> __device__ __forceinline__ float dot_row(const T *row, const float *x, int d) {
+    float s = 0.f, tmp[Vec<T>::n];
+    for (int c = 0; c < d; c += Vec<T>::n) {
+        load_vec<T>(row + c, tmp);
+#pragma unroll
+        for (int e = 0; e < Vec<T>::n; ++e) s = fmaf(tmp[e], x[c + e], s);
+    }
+    return s;
+}
+
+// ------------------------------------------------------------------------------------------------ pooling
+// Alg. 1, compression loop: out[t] = (x[tB] + x[tB+1] + ... + x[tB+B-1]) / B, summed in that order in
+// fp32, one IEEE division, one rounding to the I/O type.  The order is part of the contract: the
+// selection below is decided on these values, so they must not depend on the launch shape.
+struct PoolArgs { const void *in[3]; void *out[3]; };
+
+template <class T>
+__global__ void __launch_bounds__(256) pool_kernel(PoolArgs a, int64_t n_out_total, int d, int B) {
+    constexpr int VN = Vec<T>::n;
+    const int vpr = d / VN;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t t = idx / vpr;
+    const int cv = (int)(idx % vpr);
+    if (t >= n_out_total) return;
+    const T *in = static_cast<const T *>(a.in[blockIdx.y]) + (t * B) * (int64_t)d + cv * VN;
+    float s[VN], x[VN];
+#pragma unroll
+    for (int e = 0; e < VN; ++e) s[e] = 0.f;
+    for (int r = 0; r < B; ++r) {
+        load_vec<T>(in + (int64_t)r * d, x);
+#pragma unroll
+        for (int e = 0; e < VN; ++e) s[e] = s[e] + x[e];
+    }
+    const float Bf = (float)B;
+#pragma unroll
+    for (int e = 0; e < VN; ++e) s[e] = __fdiv_rn(s[e], Bf);
+    store_vec<T>(static_cast<T *>(a.out[blockIdx.y]) + t * (int64_t)d + cv * VN, s);
+}
+
+hipError_t launch_pool(const Plan &p, const void *Q, const void *K, const void *V, void *ws, bool q_too,
+                       hipStream_t s) {
+    const void *src[3] = {Q, K, V};
+    char *w = static_cast<char *>(ws);
+    for (int l = 1; l <= p.L; ++l) {
+        PoolArgs a;
+        int cnt = 0;
+        for (int x = q_too ? 0 : 1; x < 3; ++x, ++cnt) {
+            a.in[cnt] = (l == 1) ? src[x] : (const void *)(w + p.pyr_off[x][l - 1]);
+            a.out[cnt] = w + p.pyr_off[x][l];
+        }
+        const int64_t n_out_total = (int64_t)p.bh * p.n[l];
+        const int vn = 16 / p.elt;
+        const int64_t threads = n_out_total * (p.d / vn);
+        dim3 grid((unsigned)((threads + 255) / 256), cnt);
+        if (p.elt == 4) pool_kernel<float><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else            pool_kernel<bf16_t><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// ---------------------------------------------------------------------------------------------- selection
+// Alg. 1, selection loop, one level: every wave scores one level-l query token against its candidates
+// (all n_L tokens at the coarsest level, the K_l*B children of the parent's picks below it) and keeps the
+// Kout best.  Scores are fp32 fused-multiply-add chains over channels 0..d-1 in order, so they do not
+// depend on the launch shape; ties go to the lower key id; rows are written in ascending id order.
+template <class T>
+__global__ void select_kernel(const T *Ql, const T *Kl, int64_t n_l, int d, int B, const int32_t *parent, int Kp,
+                              int Kout, int32_t *out, int C, int64_t nblk) {
+    extern __shared__ float smem[];
+    const int W = blockDim.x >> 6, wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    float *qs = smem + wave * d;
+    float *sc = smem + W * d + (size_t)wave * C;
+    const int64_t bh = blockIdx.x / nblk, r = blockIdx.x % nblk;
+    const T *Kb = Kl + bh * n_l * d;
+    const int32_t *prow = parent ? parent + (bh * nblk + r) * Kp : nullptr;
+    const int iters = (B + W - 1) / W;
+    for (int it = 0; it < iters; ++it) {
+        const int u = it * W + wave;
+        const int64_t i = r * B + u;
+        const bool active = (u < B) && (i < n_l);
+        __syncthreads();                                   // previous row's LDS no longer read
+        if (active)
+            for (int c = lane; c < d; c += 64) qs[c] = to_f(Ql[(bh * n_l + i) * d + c]);
+        __syncthreads();
+        if (active)
+            for (int p = lane; p < C; p += 64) {
+                const int64_t id = prow ? (int64_t)prow[p / B] * B + p % B : p;
+                const T *k = Kb + id * d;
+                float s = 0.f, tmp[Vec<T>::n];
+                for (int c = 0; c < d; c += Vec<T>::n) {
+                    load_vec<T>(k + c, tmp);
+#pragma unroll
+                    for (int e = 0; e < Vec<T>::n; ++e) s = __builtin_fmaf(qs[c + e], tmp[e], s);
+                }
+                sc[p] = s;
+            }
+        int mine = 0;                                      // lane k keeps the k-th winner's position
+        for (int k = 0; k < Kout; ++k) {
+            __syncthreads();
+            float bs = -INFINITY;
+            int bp = 0x7fffffff;
+            if (active)
+                for (int p = lane; p < C; p += 64) {
+                    const float v = sc[p];
+                    if (v > bs) { bs = v; bp = p; }        // ascending p: strict '>' keeps the lowest position
+                }
+#pragma unroll
+            for (int o = 32; o >= 1; o >>= 1) {
+                const float os = __shfl_xor(bs, o, 64);
+                const int op = __shfl_xor(bp, o, 64);
+                if (os > bs || (os == bs && op < bp)) { bs = os; bp = op; }
+            }
+            if (active && lane == (bp & 63)) sc[bp] = -INFINITY;
+            if (lane == k) mine = bp;
+        }
+        if (active) {
+            // candidate positions ascend with key id (parent rows are ascending), so rank by position
+            int rank = 0;
+            for (int k = 0; k < Kout; ++k) rank += (__shfl(mine, k, 64) < mine) ? 1 : 0;
+            if (lane < Kout) {
+                const int64_t id = prow ? (int64_t)prow[mine / B] * B + mine % B : mine;
+                out[(bh * n_l + i) * Kout + rank] = (int32_t)id;
+            }
+        }
+    }
+}
+
+hipError_t launch_select(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s) {
+    const char *w = static_cast<const char *>(ws);
+    const bool top = (l == p.L);
+    const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
+    const int Kout = p.Kl[l - 1];
+    const int64_t nblk = (p.n[l] + p.B - 1) / p.B;
+    const int W = C <= 2048 ? 4 : (C <= 4096 ? 2 : 1);
+    const size_t lds = (size_t)W * (p.d + C) * sizeof(float);
+    dim3 grid((unsigned)(p.bh * nblk));
+    const int Kp = top ? 0 : p.Kl[l];
+    const void *Ql = w + p.pyr_off[0][l], *Kl = w + p.pyr_off[1][l];
+    if (p.elt == 4)
+        select_kernel<float><<<grid, W * 64, lds, s>>>((const float *)Ql, (const float *)Kl, p.n[l], p.d, p.B,
+                                                       top ? nullptr : parent, Kp, Kout, out, C, nblk);
+    else
+        select_kernel<bf16_t><<<grid, W * 64, lds, s>>>((const bf16_t *)Ql, (const bf16_t *)Kl, p.n[l], p.d, p.B,
+                                                        top ? nullptr : parent, Kp, Kout, out, C, nblk);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------------- gathered-list walk
+// Position `pos` of the list of fine query block `blk` (Alg. 1, enrichment loop): level and token id.
+__device__ __forceinline__ void list_entry(const LevelTable &t, int64_t bh, int64_t blk, int pos, int &lev,
+                                           int &tok) {
+    int l = 0;
+    while (l + 1 < t.nlev && pos >= t.seg[l + 1]) ++l;
+    const int off = pos - t.seg[l];
+    if (l < t.L) {
+        const int64_t row = blk / t.Bpow[l];
+        const int k = off / t.B, u = off % t.B;
+        tok = t.I[l][(bh * t.rows[l] + row) * t.Kl[l] + k] * t.B + u;
+    } else {
+        tok = off;
+    }
+    lev = l;
+}
+
+// ------------------------------------------------------------------------------ attention forward (scalar)
+// Eq. 1-5 restricted to the gathered list, one wave per query row, online softmax over chunks of 64 list
+// entries (lane = entry for the logits, lane = channel for the value accumulation).
+template <class T>
+__global__ void __launch_bounds__(256) attn_fwd_generic(LevelTable t, const T *Q, T *O, float *LSE, int64_t N,
+                                                         int64_t total_rows) {
+    __shared__ float qs[4][128];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, d = t.d;
+    int64_t row = (int64_t)blockIdx.x * 4 + wave;
+    const bool active = row < total_rows;
+    if (!active) row = total_rows - 1;
+    const int64_t bh = row / N, q = row % N, blk = q / t.B;
+    for (int c = lane; c < d; c += 64) qs[wave][c] = to_f(Q[row * d + c]);
+    __syncthreads();
+    const int M = t.seg[t.nlev];
+    float m = -INFINITY, lsum = 0.f, acc0 = 0.f, acc1 = 0.f;
+    for (int base = 0; base < M; base += 64) {
+        const int pos = base + lane;
+        const bool valid = pos < M;
+        int lev = 0, tok = 0;
+        float z = -INFINITY;
+        if (valid) {
+            list_entry(t, bh, blk, pos, lev, tok);
+            const T *k = static_cast<const T *>(t.K[lev]) + (bh * t.n[lev] + tok) * d;
+            z = t.scale * dot_row<T>(k, qs[wave], d) + t.bias[lev];
+        }
+        const float m_new = fmaxf(m, wave_max(z));
+        const float pr = valid ? expf(z - m_new) : 0.f;
+        const float alpha = expf(m - m_new);
+        lsum = lsum * alpha + wave_sum(pr);
+        acc0 *= alpha;
+        acc1 *= alpha;
+        m = m_new;
+        const int cnt = min(64, M - base);
+        for (int j = 0; j < cnt; ++j) {
+            const float pj = __shfl(pr, j, 64);
+            const int lj = __shfl(lev, j, 64), tj = __shfl(tok, j, 64);
+            const T *v = static_cast<const T *>(t.V[lj]) + (bh * t.n[lj] + tj) * d;
+            if (lane < d) acc0 = fmaf(pj, to_f(v[lane]), acc0);
+            if (lane + 64 < d) acc1 = fmaf(pj, to_f(v[lane + 64]), acc1);
+        }
+    }
+    if (active) {
+        const float inv = 1.f / lsum;
+        if (lane < d) O[row * d + lane] = from_f<T>(acc0 * inv);
+        if (lane + 64 < d) O[row * d + lane + 64] = from_f<T>(acc1 * inv);
+        if (lane == 0) LSE[row] = m + logf(lsum);
+    }
+}
+
+hipError_t launch_attn_fwd_generic(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
+                                   hipStream_t s) {
+    const int64_t rows = (int64_t)p.bh * p.N;
+    dim3 grid((unsigned)((rows + 3) / 4));
+    if (p.elt == 4) attn_fwd_generic<float><<<grid, 256, 0, s>>>(t, (const float *)Q, (float *)O, LSE, p.N, rows);
+    else attn_fwd_generic<bf16_t><<<grid, 256, 0, s>>>(t, (const bf16_t *)Q, (bf16_t *)O, LSE, p.N, rows);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------- D = rowsum(dO * O)
+template <class T>
+__global__ void __launch_bounds__(256) bwd_pre_kernel(const T *O, const T *dO, float *D, int64_t rows, int d) {
+    const int sub = threadIdx.x & 15;
+    int64_t row = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const bool active = row < rows;
+    if (!active) row = rows - 1;
+    float s = 0.f;
+    for (int c = sub; c < d; c += 16) s = fmaf(to_f(O[row * d + c]), to_f(dO[row * d + c]), s);
+#pragma unroll
+    for (int o = 8; o >= 1; o >>= 1) s += __shfl_xor(s, o, 64);
+    if (active && sub == 0) D[row] = s;
+}
+
+hipError_t launch_bwd_pre(const Plan &p, const void *O, const void *dO, float *D, hipStream_t s) {
+    const int64_t rows = (int64_t)p.bh * p.N;
+    dim3 grid((unsigned)((rows + 15) / 16));
+    if (p.elt == 4) bwd_pre_kernel<float><<<grid, 256, 0, s>>>((const float *)O, (const float *)dO, D, rows, p.d);
+    else bwd_pre_kernel<bf16_t><<<grid, 256, 0, s>>>((const bf16_t *)O, (const bf16_t *)dO, D, rows, p.d);
+    return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------- index transpose (Alg. 2)
+// count -> exclusive scan -> fill -> per-key ascending order.  Counting and filling use integer atomics;
+// the order they leave inside a key's list depends on timing, so a last pass sorts every list, which makes
+// the result (and with it the summation order of dK / dV) the same on every run.
+__global__ void csc_zero_kernel(int32_t *cnt, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n) cnt[i] = 0;
+}
+__global__ void csc_count_kernel(const int32_t *I, int32_t *cnt, int64_t entries_per_head, int64_t T,
+                                 int64_t total) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int64_t bh = e / entries_per_head;
+    atomicAdd(&cnt[bh * T + I[e]], 1);
+}
+// one workgroup per head: C = exclusive scan of cnt (T+1 entries), cnt reset to 0 for the fill pass
+__global__ void __launch_bounds__(1024) csc_scan_kernel(int32_t *cnt, int32_t *C, int64_t T) {
+    __shared__ int32_t wsum[16];
+    __shared__ int32_t carry;
+    const int64_t bh = blockIdx.x;
+    int32_t *cn = cnt + bh * T, *Co = C + bh * (T + 1);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    for (int64_t base = 0; base < T; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const int32_t v = i < T ? cn[i] : 0;
+        int32_t x = v;                                     // inclusive scan inside the wave
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int32_t y = __shfl_up(x, o, 64);
+            if (lane >= o) x += y;
+        }
+        if (lane == 63) wsum[wave] = x;
+        __syncthreads();
+        int32_t pre = carry;
+        for (int w2 = 0; w2 < wave; ++w2) pre += wsum[w2];
+        if (i < T) { Co[i] = pre + x - v; cn[i] = 0; }
+        __syncthreads();
+        if (threadIdx.x == 1023) carry = pre + x;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) Co[T] = carry;
+}
+__global__ void csc_fill_kernel(const int32_t *I, const int32_t *C, int32_t *cur, int32_t *Iq_tmp,
+                                int64_t entries_per_head, int Kl, int64_t T, int64_t total) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int64_t bh = e / entries_per_head, within = e % entries_per_head;
+    const int32_t key = I[e];
+    const int32_t slot = C[bh * (T + 1) + key] + atomicAdd(&cur[bh * T + key], 1);
+    Iq_tmp[bh * entries_per_head + slot] = (int32_t)(within / Kl);
+}
+// one wave per key: rank-sort its list (entries are distinct query rows)
+__global__ void __launch_bounds__(256) csc_sort_kernel(const int32_t *C, const int32_t *Iq_tmp, int32_t *Iq,
+                                                       int64_t entries_per_head, int64_t T, int64_t total_keys) {
+    const int lane = threadIdx.x & 63;
+    const int64_t key_flat = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (key_flat >= total_keys) return;
+    const int64_t bh = key_flat / T, key = key_flat % T;
+    const int32_t beg = C[bh * (T + 1) + key], end = C[bh * (T + 1) + key + 1];
+    const int32_t *src = Iq_tmp + bh * entries_per_head;
+    int32_t *dst = Iq + bh * entries_per_head;
+    for (int32_t a = beg + lane; a < end; a += 64) {
+        const int32_t x = src[a];
+        int32_t rank = 0;
+        for (int32_t b = beg; b < end; ++b) rank += (src[b] < x) ? 1 : 0;
+        dst[beg + rank] = x;
+    }
+}
+
+hipError_t launch_csc(const Plan &p, int l, const int32_t *indices, void *ws, hipStream_t s) {
+    char *w = static_cast<char *>(ws);
+    const int64_t T = p.n[l + 1];
+    const int64_t eph = T * p.Kl[l], total = eph * p.bh;
+    const int32_t *I = reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(indices) + p.idx_off[l]);
+    int32_t *cnt = (int32_t *)(w + p.cnt_off[l]), *C = (int32_t *)(w + p.C_off[l]);
+    int32_t *Iq = (int32_t *)(w + p.Iq_off[l]), *Iqt = (int32_t *)(w + p.Iqtmp_off[l]);
+    const int64_t nk = T * p.bh;
+    csc_zero_kernel<<<(unsigned)((nk + 255) / 256), 256, 0, s>>>(cnt, nk);
+    csc_count_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(I, cnt, eph, T, total);
+    csc_scan_kernel<<<p.bh, 1024, 0, s>>>(cnt, C, T);
+    csc_fill_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(I, C, cnt, Iqt, eph, p.Kl[l], T, total);
+    csc_sort_kernel<<<(unsigned)((nk + 3) / 4), 256, 0, s>>>(C, Iqt, Iq, eph, T, nk);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------- dQ (scalar path)
+// Query-major: same list walk as the forward; P recomputed from the saved logsumexp.
+template <class T>
+__global__ void __launch_bounds__(256) dq_generic(LevelTable t, const T *Q, const T *dO, const float *LSE,
+                                                   const float *D, T *dQ, int64_t N, int64_t total_rows) {
+    __shared__ float qs[4][128], gs[4][128];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, d = t.d;
+    int64_t row = (int64_t)blockIdx.x * 4 + wave;
+    const bool active = row < total_rows;
+    if (!active) row = total_rows - 1;
+    const int64_t bh = row / N, q = row % N, blk = q / t.B;
+    for (int c = lane; c < d; c += 64) { qs[wave][c] = to_f(Q[row * d + c]); gs[wave][c] = to_f(dO[row * d + c]); }
+    __syncthreads();
+    const float lse = LSE[row], delta = D[row];
+    const int M = t.seg[t.nlev];
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int base = 0; base < M; base += 64) {
+        const int pos = base + lane;
+        int lev = 0, tok = 0;
+        float ds = 0.f;
+        if (pos < M) {
+            list_entry(t, bh, blk, pos, lev, tok);
+            const int64_t off = (bh * t.n[lev] + tok) * d;
+            const float z = t.scale * dot_row<T>(static_cast<const T *>(t.K[lev]) + off, qs[wave], d) + t.bias[lev];
+            const float pr = expf(z - lse);
+            const float dp = dot_row<T>(static_cast<const T *>(t.V[lev]) + off, gs[wave], d);
+            ds = pr * (dp - delta);
+        }
+        const int cnt = min(64, M - base);
+        for (int j = 0; j < cnt; ++j) {
+            const float dj = __shfl(ds, j, 64);
+            const int lj = __shfl(lev, j, 64), tj = __shfl(tok, j, 64);
+            const T *k = static_cast<const T *>(t.K[lj]) + (bh * t.n[lj] + tj) * d;
+            if (lane < d) acc0 = fmaf(dj, to_f(k[lane]), acc0);
+            if (lane + 64 < d) acc1 = fmaf(dj, to_f(k[lane + 64]), acc1);
+        }
+    }
+    if (active) {
+        if (lane < d) dQ[row * d + lane] = from_f<T>(t.scale * acc0);
+        if (lane + 64 < d) dQ[row * d + lane + 64] = from_f<T>(t.scale * acc1);
+    }
+}
+
+hipError_t launch_dq_generic(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
+                             const float *D, void *dQ, hipStream_t s) {
+    const int64_t rows = (int64_t)p.bh * p.N;
+    dim3 grid((unsigned)((rows + 3) / 4));
+    if (p.elt == 4)
+        dq_generic<float><<<grid, 256, 0, s>>>(t, (const float *)Q, (const float *)dO, LSE, D, (float *)dQ, p.N, rows);
+    else
+        dq_generic<bf16_t><<<grid, 256, 0, s>>>(t, (const bf16_t *)Q, (const bf16_t *)dO, LSE, D, (bf16_t *)dQ, p.N,
+                                                rows);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ dK, dV (scalar path)
+// Key-major (Sec. 4.3): one wave per level-l key token walks the query blocks that listed its block
+// (lists from Alg. 2; at the coarsest enriched level L every query).  Level >= 1 results go to fp32
+// buffers; level 0 adds its parent's share (adjoint of mean pooling) and rounds once to the I/O type.
+template <class T>
+__global__ void __launch_bounds__(256) dkv_generic(LevelTable t, int l, const T *Q, const T *dO, const float *LSE,
+                                                    const float *D, const int32_t *C, const int32_t *Iq,
+                                                    float *dKacc, float *dVacc, const float *parK, const float *parV,
+                                                    T *dK, T *dV, int64_t N, int64_t total_tokens) {
+    __shared__ float ks[4][128], vs[4][128];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, d = t.d, B = t.B;
+    int64_t tf = (int64_t)blockIdx.x * 4 + wave;           // flat key token over bh * n_l
+    const bool active = tf < total_tokens;
+    if (!active) tf = total_tokens - 1;
+    const int64_t n_l = t.n[l], bh = tf / n_l, tok = tf % n_l;
+    const T *Kl = static_cast<const T *>(t.K[l]), *Vl = static_cast<const T *>(t.V[l]);
+    for (int c = lane; c < d; c += 64) { ks[wave][c] = to_f(Kl[tf * d + c]); vs[wave][c] = to_f(Vl[tf * d + c]); }
+    __syncthreads();
+    const bool dense = (l == t.L);
+    const int64_t span = dense ? 1 : t.Bpow[l + 1];        // fine queries per listed query block
+    int64_t qcount;
+    const int32_t *lst = nullptr;
+    if (dense) {
+        qcount = N;
+    } else {
+        const int64_t T_keys = t.rows[l], j = tok / B;
+        const int32_t beg = C[bh * (T_keys + 1) + j], end = C[bh * (T_keys + 1) + j + 1];
+        lst = Iq + bh * T_keys * t.Kl[l] + beg;
+        qcount = (int64_t)(end - beg) * span;
+    }
+    float dk0 = 0.f, dk1 = 0.f, dv0 = 0.f, dv1 = 0.f;
+    for (int64_t base = 0; base < qcount; base += 64) {
+        const int64_t g = base + lane;
+        float pr = 0.f, ds = 0.f;
+        int64_t qrow = 0;
+        if (g < qcount) {
+            const int64_t q = dense ? g : (int64_t)lst[g / span] * span + g % span;
+            qrow = bh * N + q;
+            const float z = t.scale * dot_row<T>(Q + qrow * d, ks[wave], d) + t.bias[l];
+            pr = expf(z - LSE[qrow]);
+            const float dp = dot_row<T>(dO + qrow * d, vs[wave], d);
+            ds = pr * (dp - D[qrow]);
+        }
+        const int cnt = (int)min((int64_t)64, qcount - base);
+        for (int j = 0; j < cnt; ++j) {
+            const float pj = __shfl(pr, j, 64), dj = __shfl(ds, j, 64);
+            const int64_t rj = __shfl(qrow, j, 64);
+            if (lane < d) {
+                dv0 = fmaf(pj, to_f(dO[rj * d + lane]), dv0);
+                dk0 = fmaf(dj, to_f(Q[rj * d + lane]), dk0);
+            }
+            if (lane + 64 < d) {
+                dv1 = fmaf(pj, to_f(dO[rj * d + lane + 64]), dv1);
+                dk1 = fmaf(dj, to_f(Q[rj * d + lane + 64]), dk1);
+            }
+        }
+    }
+    if (!active) return;
+    dk0 *= t.scale; dk1 *= t.scale;
+    if (l > 0) {
+        if (lane < d) { dKacc[tf * d + lane] = dk0; dVacc[tf * d + lane] = dv0; }
+        if (lane + 64 < d) { dKacc[tf * d + lane + 64] = dk1; dVacc[tf * d + lane + 64] = dv1; }
+    } else {
+        const float invB = 1.f / (float)B;
+        const int64_t par = (bh * t.n[1] + tok / B) * d;   // parent token at level 1
+        if (lane < d) {
+            const float pk = parK ? parK[par + lane] * invB : 0.f, pv = parV ? parV[par + lane] * invB : 0.f;
+            dK[tf * d + lane] = from_f<T>(dk0 + pk);
+            dV[tf * d + lane] = from_f<T>(dv0 + pv);
+        }
+        if (lane + 64 < d) {
+            const float pk = parK ? parK[par + lane + 64] * invB : 0.f, pv = parV ? parV[par + lane + 64] * invB : 0.f;
+            dK[tf * d + lane + 64] = from_f<T>(dk1 + pk);
+            dV[tf * d + lane + 64] = from_f<T>(dv1 + pv);
+        }
+    }
+}
+
+hipError_t launch_dkv_generic(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO,
+                              const float *LSE, const float *D, void *ws, void *dK, void *dV, hipStream_t s) {
+    char *w = static_cast<char *>(ws);
+    const int64_t total = (int64_t)p.bh * p.n[l];
+    dim3 grid((unsigned)((total + 3) / 4));
+    const int32_t *C = l < p.L ? (const int32_t *)(w + p.C_off[l]) : nullptr;
+    const int32_t *Iq = l < p.L ? (const int32_t *)(w + p.Iq_off[l]) : nullptr;
+    float *ka = l > 0 ? (float *)(w + p.dKacc_off[l]) : nullptr, *va = l > 0 ? (float *)(w + p.dVacc_off[l]) : nullptr;
+    const bool has_parent = (l == 0 && p.Le >= 1);
+    const float *pk = has_parent ? (const float *)(w + p.dKacc_off[1]) : nullptr;
+    const float *pv = has_parent ? (const float *)(w + p.dVacc_off[1]) : nullptr;
+    if (p.elt == 4)
+        dkv_generic<float><<<grid, 256, 0, s>>>(t, l, (const float *)Q, (const float *)dO, LSE, D, C, Iq, ka, va, pk, pv,
+                                                (float *)dK, (float *)dV, p.N, total);
+    else
+        dkv_generic<bf16_t><<<grid, 256, 0, s>>>(t, l, (const bf16_t *)Q, (const bf16_t *)dO, LSE, D, C, Iq, ka, va, pk,
+                                                 pv, (bf16_t *)dK, (bf16_t *)dV, p.N, total);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------ un-pool
+// Adjoint of one pooling step on the fp32 gradient buffers: level l-1 token t*B + r gains (1/B) of level-l
+// token t (l >= 2 here; the step into level 0 is folded into the level-0 dK/dV epilogue).
+__global__ void __launch_bounds__(256) unpool_kernel(float *dstK, float *dstV, const float *srcK, const float *srcV,
+                                                     int64_t total, int d, int B) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= total) return;
+    const int64_t tok = i / d, c = i % d;
+    const int64_t src = (tok / B) * d + c;                 // flat over bh: n_{l-1} = B * n_l per head
+    const float invB = 1.f / (float)B;
+    dstK[i] += srcK[src] * invB;
+    dstV[i] += srcV[src] * invB;
+}
+
+hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s) {
+    char *w = static_cast<char *>(ws);
+    const int64_t total = (int64_t)p.bh * p.n[l - 1] * p.d;
+    unpool_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(
+        (float *)(w + p.dKacc_off[l - 1]), (float *)(w + p.dVacc_off[l - 1]), (const float *)(w + p.dKacc_off[l]),
+        (const float *)(w + p.dVacc_off[l]), total, p.d, p.B);
+    return hipGetLastError();
+}
+
+}  // namespace llsa

@@ -1,0 +1,250 @@
+// C ABI of libllsa: host-side plan (validation, level table, buffer layout) and the launch sequences of
+// the forward and backward passes.  No device memory is allocated here and the host never waits.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+
+#include "llsa_internal.h"
+
+namespace llsa {
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+LevelTable make_level_table(const Plan &p, const void *K0, const void *V0, const int32_t *indices,
+                            const void *workspace) {
+    LevelTable t;
+    memset(&t, 0, sizeof(t));
+    const char *w = static_cast<const char *>(workspace);
+    const char *idx = reinterpret_cast<const char *>(indices);
+    int64_t bp = 1;
+    int pos = 0;
+    for (int l = 0; l <= p.L; ++l) {
+        t.K[l] = (l == 0) ? K0 : (const void *)(w + p.pyr_off[1][l]);
+        t.V[l] = (l == 0) ? V0 : (const void *)(w + p.pyr_off[2][l]);
+        t.I[l] = (l < p.L) ? reinterpret_cast<const int32_t *>(idx + p.idx_off[l]) : nullptr;
+        t.n[l] = p.n[l];
+        t.rows[l] = (l < p.L) ? p.n[l + 1] : 0;
+        t.Kl[l] = (l < p.L) ? p.Kl[l] : 0;
+        t.Bpow[l] = bp;
+        t.bias[l] = p.desc.reweight ? (float)(l * log((double)p.B)) : 0.f;
+        if (l <= p.Le) {
+            t.seg[l] = pos;
+            pos += (l < p.L) ? p.Kl[l] * p.B : (int)p.n[l];
+        }
+        bp *= p.B;
+    }
+    t.Bpow[p.L + 1] = bp;
+    t.nlev = p.Le + 1;
+    t.seg[t.nlev] = pos;
+    t.L = p.L;
+    t.B = p.B;
+    t.d = p.d;
+    t.scale = p.scale;
+    return t;
+}
+
+static llsa_status build_plan(const llsa_desc &d, Plan &p) {
+    memset(&p, 0, sizeof(p));
+    p.desc = d;
+    if (d.batch < 1 || d.heads < 1 || d.N < 1 || d.K < 1 || d.L < 1 || d.B < 2) return LLSA_ERR_BAD_SHAPE;
+    if (d.Le < 0 || d.Le > d.L) return LLSA_ERR_BAD_SHAPE;
+    if (d.dtype != LLSA_F32 && d.dtype != LLSA_BF16) return LLSA_ERR_UNSUPPORTED;
+    if (d.d != 16 && d.d != 32 && d.d != 64 && d.d != 128) return LLSA_ERR_UNSUPPORTED;
+    if (d.B > 64 || d.K > 64 || d.L > kMaxL) return LLSA_ERR_UNSUPPORTED;
+    if (d.N > ((int64_t)1 << 30) || (int64_t)d.batch * d.heads > (1 << 20)) return LLSA_ERR_UNSUPPORTED;
+    int64_t bl = 1;
+    for (int l = 0; l < d.L; ++l) {
+        bl *= d.B;
+        if (bl > d.N) return LLSA_ERR_BAD_SHAPE;
+    }
+    if (d.N % bl != 0) return LLSA_ERR_BAD_SHAPE;
+    p.L = d.L; p.Le = d.Le; p.B = d.B; p.K = d.K; p.d = d.d; p.N = d.N;
+    p.bh = d.batch * d.heads;
+    p.elt = d.dtype == LLSA_F32 ? 4 : 2;
+    p.scale = d.sm_scale > 0.f ? d.sm_scale : (float)(1.0 / sqrt((double)d.d));
+    int64_t nl = d.N;
+    for (int l = 0; l <= p.L; ++l) { p.n[l] = nl; nl /= d.B; }
+    size_t off = 0;
+    for (int l = 0; l < p.L; ++l) {
+        p.Kl[l] = (int)(p.n[l + 1] < d.K ? p.n[l + 1] : d.K);
+        p.idx_off[l] = off;
+        off += (size_t)p.bh * p.n[l + 1] * p.Kl[l] * sizeof(int32_t);
+    }
+    p.idx_bytes = off;
+    // selection holds one row of candidate scores per wave in LDS
+    if (p.n[p.L] > kMaxCand) return LLSA_ERR_UNSUPPORTED;
+    for (int l = 1; l < p.L; ++l)
+        if ((int64_t)p.Kl[l] * p.B > kMaxCand) return LLSA_ERR_UNSUPPORTED;
+    int64_t m = 0;
+    for (int l = 0; l <= p.Le; ++l) m += (l < p.L) ? (int64_t)p.Kl[l] * p.B : p.n[l];
+    p.list_len = (int)m;
+
+    // ---- workspace: pooled levels first (shared by forward and backward) ----
+    size_t ws = 0;
+    for (int x = 0; x < 3; ++x)
+        for (int l = 1; l <= p.L; ++l) {
+            p.pyr_off[x][l] = ws;
+            ws = align_up(ws + (size_t)p.bh * p.n[l] * p.d * p.elt);
+        }
+    p.ws_fwd = ws;
+    p.D_off = ws;
+    ws = align_up(ws + (size_t)p.bh * p.N * sizeof(float));
+    for (int l = 0; l < p.L; ++l) {
+        const size_t keys = (size_t)p.bh * p.n[l + 1], ent = keys * p.Kl[l];
+        p.C_off[l] = ws;     ws = align_up(ws + ((size_t)p.bh * (p.n[l + 1] + 1)) * sizeof(int32_t));
+        p.cnt_off[l] = ws;   ws = align_up(ws + keys * sizeof(int32_t));
+        p.Iq_off[l] = ws;    ws = align_up(ws + ent * sizeof(int32_t));
+        p.Iqtmp_off[l] = ws; ws = align_up(ws + ent * sizeof(int32_t));
+    }
+    for (int l = 1; l <= p.L; ++l) {
+        const size_t bytes = (size_t)p.bh * p.n[l] * p.d * sizeof(float);
+        p.dKacc_off[l] = ws; ws = align_up(ws + bytes);
+        p.dVacc_off[l] = ws; ws = align_up(ws + bytes);
+    }
+    p.part_off = ws;
+    p.part_bytes = 0;
+    p.ws_bwd = ws;
+    p.fast = false;
+    return LLSA_OK;
+}
+
+}  // namespace llsa
+
+using namespace llsa;
+
+struct llsa_plan_s { Plan p; };
+
+extern "C" {
+
+llsa_status llsa_plan(const llsa_desc *desc, llsa_plan_t **out) {
+    if (!desc || !out) return LLSA_ERR_NULL;
+    *out = nullptr;
+    Plan p;
+    llsa_status st = build_plan(*desc, p);
+    if (st != LLSA_OK) return st;
+    llsa_plan_s *h = new (std::nothrow) llsa_plan_s;
+    if (!h) return LLSA_ERR_RUNTIME;
+    h->p = p;
+    *out = h;
+    return LLSA_OK;
+}
+
+void llsa_plan_destroy(llsa_plan_t *plan) { delete plan; }
+
+size_t llsa_plan_workspace_bytes(const llsa_plan_t *plan, int for_backward) {
+    if (!plan) return 0;
+    return for_backward ? plan->p.ws_bwd : plan->p.ws_fwd;
+}
+
+size_t llsa_plan_indices_bytes(const llsa_plan_t *plan) { return plan ? plan->p.idx_bytes : 0; }
+
+int32_t llsa_plan_level_info(const llsa_plan_t *plan, int32_t l, int64_t *rows, int32_t *K_l, size_t *byte_offset) {
+    if (!plan || l < 0 || l >= plan->p.L) return -1;
+    if (rows) *rows = plan->p.n[l + 1];
+    if (K_l) *K_l = plan->p.Kl[l];
+    if (byte_offset) *byte_offset = plan->p.idx_off[l];
+    return plan->p.L;
+}
+
+int32_t llsa_plan_pyramid_info(const llsa_plan_t *plan, int32_t tensor, int32_t l, int64_t *tokens,
+                               size_t *byte_offset) {
+    if (!plan || tensor < 0 || tensor > 2 || l < 1 || l > plan->p.L) return -1;
+    if (tokens) *tokens = plan->p.n[l];
+    if (byte_offset) *byte_offset = plan->p.pyr_off[tensor][l];
+    return 0;
+}
+
+int32_t llsa_plan_csc_info(const llsa_plan_t *plan, int32_t l, size_t *C_byte_offset, size_t *Iq_byte_offset) {
+    if (!plan || l < 0 || l >= plan->p.L) return -1;
+    if (C_byte_offset) *C_byte_offset = plan->p.C_off[l];
+    if (Iq_byte_offset) *Iq_byte_offset = plan->p.Iq_off[l];
+    return 0;
+}
+
+#define LLSA_TRY(expr)                                   \
+    do {                                                 \
+        if ((expr) != hipSuccess) return LLSA_ERR_RUNTIME; \
+    } while (0)
+
+llsa_status llsa_pool(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *workspace,
+                      void *hip_stream) {
+    if (!plan || !Q || !K || !V || !workspace) return LLSA_ERR_NULL;
+    LLSA_TRY(launch_pool(plan->p, Q, K, V, workspace, true, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
+llsa_status llsa_select_level(const llsa_plan_t *plan, int32_t l, const void *workspace, const int32_t *parent,
+                              int32_t *out, void *hip_stream) {
+    if (!plan || !workspace || !out) return LLSA_ERR_NULL;
+    if (l < 1 || l > plan->p.L) return LLSA_ERR_BAD_SHAPE;
+    if (l < plan->p.L && !parent) return LLSA_ERR_NULL;
+    LLSA_TRY(launch_select(plan->p, l, workspace, parent, out, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
+llsa_status llsa_attention(const llsa_plan_t *plan, const void *Q, const void *K, const void *V,
+                           const int32_t *indices, const void *workspace, void *O, float *LSE, void *hip_stream) {
+    if (!plan || !Q || !K || !V || !indices || !workspace || !O || !LSE) return LLSA_ERR_NULL;
+    const Plan &p = plan->p;
+    LevelTable t = make_level_table(p, K, V, indices, workspace);
+    LLSA_TRY(launch_attn_fwd_generic(p, t, Q, O, LSE, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
+llsa_status llsa_forward(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O, float *LSE,
+                         int32_t *indices, void *workspace, void *hip_stream) {
+    if (!plan || !Q || !K || !V || !O || !LSE || !indices || !workspace) return LLSA_ERR_NULL;
+    const Plan &p = plan->p;
+    hipStream_t s = (hipStream_t)hip_stream;
+    LLSA_TRY(launch_pool(p, Q, K, V, workspace, true, s));
+    char *idx = reinterpret_cast<char *>(indices);
+    for (int l = p.L; l >= 1; --l) {
+        const int32_t *parent = (l < p.L) ? reinterpret_cast<const int32_t *>(idx + p.idx_off[l]) : nullptr;
+        LLSA_TRY(launch_select(p, l, workspace, parent, reinterpret_cast<int32_t *>(idx + p.idx_off[l - 1]), s));
+    }
+    return llsa_attention(plan, Q, K, V, indices, workspace, O, LSE, hip_stream);
+}
+
+llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices, void *workspace, void *hip_stream) {
+    if (!plan || !indices || !workspace) return LLSA_ERR_NULL;
+    const Plan &p = plan->p;
+    for (int l = 0; l < p.L; ++l) LLSA_TRY(launch_csc(p, l, indices, workspace, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
+llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, const void *O,
+                          const float *LSE, const int32_t *indices, const void *dO, void *dQ, void *dK, void *dV,
+                          void *workspace, void *hip_stream) {
+    if (!plan || !Q || !K || !V || !O || !LSE || !indices || !dO || !dQ || !dK || !dV || !workspace)
+        return LLSA_ERR_NULL;
+    const Plan &p = plan->p;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *w = static_cast<char *>(workspace);
+    if (p.desc.bwd_repool) LLSA_TRY(launch_pool(p, Q, K, V, workspace, false, s));
+    float *D = reinterpret_cast<float *>(w + p.D_off);
+    LLSA_TRY(launch_bwd_pre(p, O, dO, D, s));
+    const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
+    for (int l = 0; l <= top_listed; ++l) LLSA_TRY(launch_csc(p, l, indices, workspace, s));
+    LevelTable t = make_level_table(p, K, V, indices, workspace);
+    LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
+    // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
+    for (int l = p.Le; l >= 1; --l) LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+    for (int l = p.Le; l >= 2; --l) LLSA_TRY(launch_unpool(p, l, workspace, s));
+    LLSA_TRY(launch_dkv_generic(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
+    return LLSA_OK;
+}
+
+const char *llsa_status_string(llsa_status s) {
+    switch (s) {
+        case LLSA_OK: return "ok";
+        case LLSA_ERR_NULL: return "null pointer";
+        case LLSA_ERR_BAD_SHAPE: return "bad shape (N must be divisible by B^L; L >= 1; 0 <= Le <= L; K >= 1)";
+        case LLSA_ERR_UNSUPPORTED: return "unsupported d / B / K / dtype / size";
+        case LLSA_ERR_WORKSPACE: return "workspace error";
+        case LLSA_ERR_RUNTIME: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

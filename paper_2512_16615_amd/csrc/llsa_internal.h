@@ -1,0 +1,67 @@
+// Internal declarations shared by the translation units of libllsa (host plan + kernel launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/llsa.h"
+
+namespace llsa {
+
+constexpr int kMaxL = 8;            // coarse levels supported (levels 0..8)
+constexpr int kMaxCand = 4096;      // candidates per selection row held in LDS (n_L or K_l * B)
+
+// Host-side description of one problem: level table and buffer layout.
+struct Plan {
+    llsa_desc desc;
+    int L, Le, B, K, d, bh, elt;    // elt = bytes per element of the I/O type
+    int64_t N;
+    float scale;
+    int64_t n[kMaxL + 1];           // tokens per head at level l
+    int Kl[kMaxL];                  // K_l = min(K, n_{l+1})
+    size_t idx_off[kMaxL];          // byte offset of I^(l) inside `indices`
+    size_t idx_bytes;
+    size_t pyr_off[3][kMaxL + 1];   // workspace byte offset of pooled level l (1..L) of Q/K/V
+    size_t D_off;                   // [bh, N] fp32: rowsum(dO * O)
+    size_t C_off[kMaxL], cnt_off[kMaxL], Iq_off[kMaxL], Iqtmp_off[kMaxL];
+    size_t dKacc_off[kMaxL + 1], dVacc_off[kMaxL + 1]; // fp32 gradients of pooled level l (1..L)
+    size_t part_off, part_bytes;    // partial sums of split key-major reductions
+    size_t ws_fwd, ws_bwd;
+    int list_len;                   // tokens one query attends to
+    bool fast;                      // MFMA kernels apply (bf16, B = 16, d in {64, 128})
+};
+
+// What the attention-type kernels need to walk the gathered list of a query block.
+struct LevelTable {
+    const void *K[kMaxL + 1];       // level-l keys   [bh, n_l, d]
+    const void *V[kMaxL + 1];       // level-l values [bh, n_l, d]
+    const int32_t *I[kMaxL + 1];    // I^(l) [bh, rows_l, K_l]; unused for l = L
+    int64_t n[kMaxL + 1];
+    int64_t rows[kMaxL + 1];
+    int64_t Bpow[kMaxL + 2];        // B^l
+    int Kl[kMaxL + 1];
+    int seg[kMaxL + 2];             // list position where level l starts; seg[nlev] = list length
+    float bias[kMaxL + 1];          // l * ln B (or 0)
+    int nlev;                       // levels in the list = Le + 1
+    int L, B, d;
+    float scale;
+};
+
+LevelTable make_level_table(const Plan &p, const void *K0, const void *V0, const int32_t *indices,
+                            const void *workspace);
+
+// ---- portable scalar kernels (any supported shape) ----
+hipError_t launch_pool(const Plan &p, const void *Q, const void *K, const void *V, void *ws, bool q_too,
+                       hipStream_t s);
+hipError_t launch_select(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s);
+hipError_t launch_attn_fwd_generic(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
+                                   hipStream_t s);
+hipError_t launch_bwd_pre(const Plan &p, const void *O, const void *dO, float *D, hipStream_t s);
+hipError_t launch_csc(const Plan &p, int l, const int32_t *I, void *ws, hipStream_t s);
+hipError_t launch_dq_generic(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
+                             const float *D, void *dQ, hipStream_t s);
+hipError_t launch_dkv_generic(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO,
+                              const float *LSE, const float *D, void *ws, void *dK, void *dV, hipStream_t s);
+hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
+
+}  // namespace llsa

@@ -1,0 +1,81 @@
+"""Host-side checks of the C-ABI library: it loads, exports every symbol the header declares, and the plan
+validates shapes and lays out buffers without touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def llsa():
+    from paper_2512_16615_amd import build, llsa as binding
+    if not os.path.exists(binding.LIB_PATH):
+        build.build(verbose=False)
+    binding.load()
+    return binding
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "llsa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(llsa_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(llsa):
+    lib = ctypes.CDLL(llsa.LIB_PATH)
+    names = _declared_functions()
+    assert "llsa_forward" in names and "llsa_backward" in names and "llsa_plan" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(llsa.EXPORTS) == names
+
+
+def test_plan_level_table_headline(llsa):
+    p = llsa.Plan(1, 16, 65536, 64, 16, 8, 3)
+    assert [(li.rows, li.K_l) for li in p.levels] == [(4096, 8), (256, 8), (16, 8)]
+    assert p.indices_bytes() == 16 * (4096 + 256 + 16) * 8 * 4
+    pooled = 3 * 16 * (4096 + 256 + 16) * 64 * 2
+    assert pooled <= p.workspace_bytes(False) <= pooled + 9 * 256
+    assert p.workspace_bytes(True) > p.workspace_bytes(False)
+    for x in range(3):
+        assert p.pyramid_info(x, 1)[0] == 4096 and p.pyramid_info(x, 3)[0] == 16
+
+
+def test_plan_partial_top_level(llsa):
+    p = llsa.Plan(2, 16, 16384, 64, 16, 8, 3)          # top level holds 4 tokens: K_2 = 4
+    assert [(li.rows, li.K_l) for li in p.levels] == [(1024, 8), (64, 8), (4, 4)]
+    p = llsa.Plan(1, 1, 256, 32, 4, 2, 3, dtype=llsa.F32)
+    assert [(li.rows, li.K_l) for li in p.levels] == [(64, 2), (16, 2), (4, 2)]
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(N=65536 + 16), 2),          # not divisible by B^L
+    (dict(L=0), 2),
+    (dict(Le=4), 2),
+    (dict(K=0), 2),
+    (dict(d=48), 3),
+    (dict(dtype=7), 3),
+    (dict(B=128), 3),
+    (dict(L=1), 3),                    # 4096 coarse tokens: fine;  see below
+])
+def test_plan_rejects_bad_problems(llsa, kw, status):
+    args = dict(batch=1, heads=16, N=65536, d=64, B=16, K=8, L=3, Le=None)
+    args.update(kw)
+    if kw == dict(L=1):
+        llsa.Plan(**args)             # single-level selection over 4096 coarse tokens is supported
+        return
+    with pytest.raises(llsa.LlsaError) as e:
+        llsa.Plan(**args)
+    assert f"status {status}" in str(e.value)
+
+
+def test_null_pointers_are_refused_before_any_launch(llsa):
+    p = llsa.Plan(1, 1, 256, 32, 4, 2, 3, dtype=llsa.F32)
+    lib = llsa.load()
+    assert lib.llsa_forward(p._h, None, None, None, None, None, None, None, None) == 1
+    assert lib.llsa_backward(p._h, *([None] * 12)) == 1
+    assert lib.llsa_plan(None, None) == 1
+    assert lib.llsa_status_string(0) == b"ok"
