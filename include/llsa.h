@@ -136,6 +136,20 @@ llsa_status llsa_attention(const llsa_plan_t *plan, const void *Q, const void *K
 /* Alg. 2 for every level: builds the key-major lists inside the backward workspace. */
 llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices, void *workspace, void *hip_stream);
 
+/* ---- per-stage timing for benchmarks (Sec. 5.4 reports kernel-level speed; this is how it is read here) ----
+ * Stages: 0 pool, 1 select, 2 attention forward, 3 D = rowsum(dO*O), 4 index transpose, 5 dQ,
+ * 6 dK/dV of the coarse levels, 7 un-pooling, 8 dK/dV of level 0.
+ * llsa_stage_timing_begin creates HIP events (host objects, no device memory); until
+ * llsa_stage_timing_end, every llsa_forward / llsa_backward call brackets stage `stage` (-1: every stage)
+ * with two events on its stream, for at most `max_calls` calls of each.  llsa_stage_timing_end waits for
+ * the recorded events, adds the elapsed milliseconds of stage i into ms_sum[i] and the number of
+ * brackets into brackets[i] (HOST arrays of llsa_stage_count() entries, overwritten), and destroys the
+ * events.  Process-global, not thread-safe: a benchmarking aid, not part of the compute path. */
+int32_t llsa_stage_count(void);
+const char *llsa_stage_name(int32_t stage);
+llsa_status llsa_stage_timing_begin(int32_t stage, int32_t max_calls);
+llsa_status llsa_stage_timing_end(double *ms_sum, int32_t *brackets);
+
 const char *llsa_status_string(llsa_status s);
 
 #ifdef __cplusplus

@@ -288,10 +288,13 @@ int llsa_oracle_attn_fwd(const double *Q, const double *Kpyr, const double *Vpyr
  *   dQ            : [N, d]            (overwritten)
  *   dKpyr, dVpyr  : [sum_l n_l, d]    (overwritten) gradients w.r.t. every
  *                   pyramid level taken as an independent variable
+ *   q_begin,q_end : only these query rows contribute (the whole sum is
+ *                   0..N; a sub-range gives that range's share of dK, dV
+ *                   and its rows of dQ, the other rows of dQ stay zero)
  */
 int llsa_oracle_attn_bwd(const double *Q, const double *Kpyr, const double *Vpyr, const int32_t *idx,
                          const double *dO, int64_t N, int d, int B, int K, int L, int Le, int reweight,
-                         double scale, double *dQ, double *dKpyr, double *dVpyr)
+                         double scale, int64_t q_begin, int64_t q_end, double *dQ, double *dKpyr, double *dVpyr)
 {
     if (reweight != 0 && reweight != 1) return 1;
     int64_t cap = llsa_oracle_list_len(N, B, K, L, Le);
@@ -304,7 +307,7 @@ int llsa_oracle_attn_bwd(const double *Q, const double *Kpyr, const double *Vpyr
     memset(dQ, 0, sizeof(double) * (size_t)(N * d));
     memset(dKpyr, 0, sizeof(double) * (size_t)(tot * d));
     memset(dVpyr, 0, sizeof(double) * (size_t)(tot * d));
-    for (int64_t q = 0; q < N; ++q) {
+    for (int64_t q = q_begin; q < q_end; ++q) {
         int64_t m = llsa_oracle_kv_list(idx, N, B, K, L, Le, q / B, lev, tok);
         const double *qv = Q + q * d, *go = dO + q * d;
         double lse = row_logits(qv, Kpyr, N, d, B, reweight, scale, m, lev, tok, z);

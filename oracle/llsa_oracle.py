@@ -180,20 +180,23 @@ def attn_fwd(Q, Kpyr, Vpyr, idx_cat, g: Geometry, Le: int, reweight: int = 1, sc
     return O, LSE
 
 
-def attn_bwd(Q, Kpyr, Vpyr, idx_cat, dO, g: Geometry, Le: int, reweight: int = 1, scale: float | None = None):
-    """Gradients w.r.t. Q and every pyramid level (indices frozen), fp64."""
+def attn_bwd(Q, Kpyr, Vpyr, idx_cat, dO, g: Geometry, Le: int, reweight: int = 1, scale: float | None = None,
+             rows: tuple[int, int] | None = None):
+    """Gradients w.r.t. Q and every pyramid level (indices frozen), fp64.  ``rows=(a, b)`` restricts the sum to
+    the contributions of query rows ``a..b-1``."""
     Q = np.ascontiguousarray(Q, dtype=np.float64)
     Kpyr = np.ascontiguousarray(Kpyr, dtype=np.float64)
     Vpyr = np.ascontiguousarray(Vpyr, dtype=np.float64)
     dO = np.ascontiguousarray(dO, dtype=np.float64)
     scale = 1.0 / math.sqrt(g.d) if scale is None else scale
+    a, b = rows if rows is not None else (0, g.N)
     dQ = np.empty_like(Q)
     dKpyr = np.empty_like(Kpyr)
     dVpyr = np.empty_like(Vpyr)
     rc = _load().llsa_oracle_attn_bwd(_p(Q, ctypes.c_double), _p(Kpyr, ctypes.c_double), _p(Vpyr, ctypes.c_double),
                                       _p(idx_cat, ctypes.c_int32), _p(dO, ctypes.c_double), ctypes.c_int64(g.N),
                                       g.d, g.B, g.K, g.L, Le, reweight, ctypes.c_double(scale),
-                                      _p(dQ, ctypes.c_double), _p(dKpyr, ctypes.c_double), _p(dVpyr, ctypes.c_double))
+                                      ctypes.c_int64(a), ctypes.c_int64(b), _p(dQ, ctypes.c_double), _p(dKpyr, ctypes.c_double), _p(dVpyr, ctypes.c_double))
     if rc != 0:
         raise RuntimeError(f"llsa_oracle_attn_bwd failed ({rc})")
     return dQ, dKpyr, dVpyr

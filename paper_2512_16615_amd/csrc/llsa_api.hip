@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <new>
+#include <vector>
 
 #include "llsa_internal.h"
 
@@ -109,6 +110,37 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
     return LLSA_OK;
 }
 
+// ---- optional stage timing (benchmark aid) ----
+enum Stage { kPool = 0, kSelect, kAttnFwd, kBwdPre, kTranspose, kDq, kDkvCoarse, kUnpool, kDkvFine, kStages };
+static const char *const kStageNames[kStages] = {"pool", "select", "attn_fwd", "bwd_pre", "index_transpose",
+                                                 "dq", "dkv_coarse", "unpool", "dkv_fine"};
+struct StageTimer {
+    bool on = false;
+    int filter = -1, max_calls = 0, fwd_calls = 0, bwd_calls = 0;
+    std::vector<hipEvent_t> ev;          // [max_calls][kStages][2]
+    std::vector<unsigned char> rec;      // [max_calls][kStages]: 1 = begin recorded, 2 = both
+};
+static StageTimer g_timer;
+
+// Brackets one stage of one call; does nothing unless timing is on.
+struct StageScope {
+    hipEvent_t end = nullptr;
+    hipStream_t s;
+    unsigned char *flag = nullptr;
+    StageScope(int stage, int call, hipStream_t stream) : s(stream) {
+        StageTimer &t = g_timer;
+        if (!t.on || call >= t.max_calls || (t.filter >= 0 && t.filter != stage)) return;
+        const size_t i = (size_t)call * kStages + stage;
+        if (hipEventRecord(t.ev[2 * i], s) != hipSuccess) return;
+        end = t.ev[2 * i + 1];
+        flag = &t.rec[i];
+        *flag = 1;
+    }
+    ~StageScope() {
+        if (end && hipEventRecord(end, s) == hipSuccess) *flag = 2;
+    }
+};
+
 }  // namespace llsa
 
 using namespace llsa;
@@ -197,12 +229,20 @@ llsa_status llsa_forward(const llsa_plan_t *plan, const void *Q, const void *K, 
     if (!plan || !Q || !K || !V || !O || !LSE || !indices || !workspace) return LLSA_ERR_NULL;
     const Plan &p = plan->p;
     hipStream_t s = (hipStream_t)hip_stream;
-    LLSA_TRY(launch_pool(p, Q, K, V, workspace, true, s));
-    char *idx = reinterpret_cast<char *>(indices);
-    for (int l = p.L; l >= 1; --l) {
-        const int32_t *parent = (l < p.L) ? reinterpret_cast<const int32_t *>(idx + p.idx_off[l]) : nullptr;
-        LLSA_TRY(launch_select(p, l, workspace, parent, reinterpret_cast<int32_t *>(idx + p.idx_off[l - 1]), s));
+    const int call = g_timer.on ? g_timer.fwd_calls++ : 0;
+    {
+        StageScope sc(kPool, call, s);
+        LLSA_TRY(launch_pool(p, Q, K, V, workspace, true, s));
     }
+    {
+        StageScope sc(kSelect, call, s);
+        char *idx = reinterpret_cast<char *>(indices);
+        for (int l = p.L; l >= 1; --l) {
+            const int32_t *parent = (l < p.L) ? reinterpret_cast<const int32_t *>(idx + p.idx_off[l]) : nullptr;
+            LLSA_TRY(launch_select(p, l, workspace, parent, reinterpret_cast<int32_t *>(idx + p.idx_off[l - 1]), s));
+        }
+    }
+    StageScope sc(kAttnFwd, call, s);
     return llsa_attention(plan, Q, K, V, indices, workspace, O, LSE, hip_stream);
 }
 
@@ -221,18 +261,79 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     const Plan &p = plan->p;
     hipStream_t s = (hipStream_t)hip_stream;
     char *w = static_cast<char *>(workspace);
-    if (p.desc.bwd_repool) LLSA_TRY(launch_pool(p, Q, K, V, workspace, false, s));
+    const int call = g_timer.on ? g_timer.bwd_calls++ : 0;
+    if (p.desc.bwd_repool) {
+        StageScope sc(kPool, call, s);
+        LLSA_TRY(launch_pool(p, Q, K, V, workspace, false, s));
+    }
     float *D = reinterpret_cast<float *>(w + p.D_off);
-    LLSA_TRY(launch_bwd_pre(p, O, dO, D, s));
-    const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
-    for (int l = 0; l <= top_listed; ++l) LLSA_TRY(launch_csc(p, l, indices, workspace, s));
+    {
+        StageScope sc(kBwdPre, call, s);
+        LLSA_TRY(launch_bwd_pre(p, O, dO, D, s));
+    }
+    {
+        StageScope sc(kTranspose, call, s);
+        const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
+        for (int l = 0; l <= top_listed; ++l) LLSA_TRY(launch_csc(p, l, indices, workspace, s));
+    }
     LevelTable t = make_level_table(p, K, V, indices, workspace);
-    LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
+    {
+        StageScope sc(kDq, call, s);
+        LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
+    }
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
-    for (int l = p.Le; l >= 1; --l) LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
-    for (int l = p.Le; l >= 2; --l) LLSA_TRY(launch_unpool(p, l, workspace, s));
+    {
+        StageScope sc(kDkvCoarse, call, s);
+        for (int l = p.Le; l >= 1; --l) LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+    }
+    {
+        StageScope sc(kUnpool, call, s);
+        for (int l = p.Le; l >= 2; --l) LLSA_TRY(launch_unpool(p, l, workspace, s));
+    }
+    StageScope sc(kDkvFine, call, s);
     LLSA_TRY(launch_dkv_generic(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
     return LLSA_OK;
+}
+
+int32_t llsa_stage_count(void) { return kStages; }
+
+const char *llsa_stage_name(int32_t stage) { return (stage >= 0 && stage < kStages) ? kStageNames[stage] : ""; }
+
+llsa_status llsa_stage_timing_begin(int32_t stage, int32_t max_calls) {
+    StageTimer &t = g_timer;
+    if (t.on || max_calls < 1 || max_calls > 4096 || stage >= kStages) return LLSA_ERR_BAD_SHAPE;
+    const size_t n = (size_t)max_calls * kStages;
+    t.ev.assign(2 * n, nullptr);
+    t.rec.assign(n, 0);
+    for (size_t i = 0; i < 2 * n; ++i)
+        if (hipEventCreate(&t.ev[i]) != hipSuccess) {
+            for (size_t j = 0; j < i; ++j) (void)hipEventDestroy(t.ev[j]);
+            t.ev.clear();
+            return LLSA_ERR_RUNTIME;
+        }
+    t.filter = stage; t.max_calls = max_calls; t.fwd_calls = t.bwd_calls = 0; t.on = true;
+    return LLSA_OK;
+}
+
+llsa_status llsa_stage_timing_end(double *ms_sum, int32_t *brackets) {
+    StageTimer &t = g_timer;
+    if (!t.on) return LLSA_ERR_BAD_SHAPE;
+    if (!ms_sum || !brackets) return LLSA_ERR_NULL;
+    llsa_status st = LLSA_OK;
+    for (int i = 0; i < kStages; ++i) { ms_sum[i] = 0.0; brackets[i] = 0; }
+    for (int c = 0; c < t.max_calls; ++c)
+        for (int i = 0; i < kStages; ++i) {
+            const size_t k = (size_t)c * kStages + i;
+            if (t.rec[k] != 2) continue;
+            float ms = 0.f;
+            if (hipEventSynchronize(t.ev[2 * k + 1]) != hipSuccess ||
+                hipEventElapsedTime(&ms, t.ev[2 * k], t.ev[2 * k + 1]) != hipSuccess) { st = LLSA_ERR_RUNTIME; continue; }
+            ms_sum[i] += ms;
+            brackets[i] += 1;
+        }
+    for (hipEvent_t e : t.ev) (void)hipEventDestroy(e);
+    t.ev.clear(); t.rec.clear(); t.on = false;
+    return st;
 }
 
 const char *llsa_status_string(llsa_status s) {

@@ -32,7 +32,8 @@ class _Desc(ctypes.Structure):
 
 EXPORTS = ["llsa_plan", "llsa_plan_destroy", "llsa_plan_workspace_bytes", "llsa_plan_indices_bytes",
            "llsa_plan_level_info", "llsa_plan_pyramid_info", "llsa_plan_csc_info", "llsa_forward", "llsa_backward",
-           "llsa_pool", "llsa_select_level", "llsa_attention", "llsa_index_transpose", "llsa_status_string"]
+           "llsa_pool", "llsa_select_level", "llsa_attention", "llsa_index_transpose", "llsa_status_string",
+           "llsa_stage_count", "llsa_stage_name", "llsa_stage_timing_begin", "llsa_stage_timing_end"]
 
 
 def load():
@@ -70,6 +71,14 @@ def load():
     lib.llsa_attention.restype = ctypes.c_int
     lib.llsa_index_transpose.argtypes = [vp] * 4
     lib.llsa_index_transpose.restype = ctypes.c_int
+    lib.llsa_stage_count.argtypes = []
+    lib.llsa_stage_count.restype = i32
+    lib.llsa_stage_name.argtypes = [i32]
+    lib.llsa_stage_name.restype = ctypes.c_char_p
+    lib.llsa_stage_timing_begin.argtypes = [i32, i32]
+    lib.llsa_stage_timing_begin.restype = ctypes.c_int
+    lib.llsa_stage_timing_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(i32)]
+    lib.llsa_stage_timing_end.restype = ctypes.c_int
     lib.llsa_status_string.argtypes = [ctypes.c_int]
     lib.llsa_status_string.restype = ctypes.c_char_p
     _lib = lib
@@ -231,3 +240,25 @@ def attention(p: Plan, Q, K, V, indices, workspace, O=None, LSE=None):
 def index_transpose(p: Plan, indices, workspace):
     """``llsa_index_transpose``: key-major lists of every level into a backward workspace."""
     _check(load().llsa_index_transpose(p._h, _ptr(indices), _ptr(workspace), _stream()), "llsa_index_transpose")
+
+
+def stage_names() -> list[str]:
+    lib = load()
+    return [lib.llsa_stage_name(i).decode() for i in range(lib.llsa_stage_count())]
+
+
+def stage_timing_begin(stage: int | str = -1, max_calls: int = 64):
+    """``llsa_stage_timing_begin``: bracket one stage (index or name; -1 = all) with HIP events."""
+    if isinstance(stage, str):
+        stage = stage_names().index(stage)
+    _check(load().llsa_stage_timing_begin(stage, max_calls), "llsa_stage_timing_begin")
+
+
+def stage_timing_end() -> dict[str, tuple[float, int]]:
+    """``llsa_stage_timing_end``: ``{stage name: (summed ms, number of brackets)}``."""
+    lib = load()
+    n = lib.llsa_stage_count()
+    ms = (ctypes.c_double * n)()
+    cnt = (ctypes.c_int32 * n)()
+    _check(lib.llsa_stage_timing_end(ms, cnt), "llsa_stage_timing_end")
+    return {name: (ms[i], cnt[i]) for i, name in enumerate(stage_names())}
