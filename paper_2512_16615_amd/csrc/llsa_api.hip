@@ -106,7 +106,7 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
     p.part_off = ws;
     p.part_bytes = 0;
     p.ws_bwd = ws;
-    p.fast = false;
+    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && d.B == 16 && (d.d == 64 || d.d == 128);
     return LLSA_OK;
 }
 
@@ -220,7 +220,8 @@ llsa_status llsa_attention(const llsa_plan_t *plan, const void *Q, const void *K
     if (!plan || !Q || !K || !V || !indices || !workspace || !O || !LSE) return LLSA_ERR_NULL;
     const Plan &p = plan->p;
     LevelTable t = make_level_table(p, K, V, indices, workspace);
-    LLSA_TRY(launch_attn_fwd_generic(p, t, Q, O, LSE, (hipStream_t)hip_stream));
+    if (p.fast) LLSA_TRY(launch_attn_fwd_mfma(p, t, Q, O, LSE, (hipStream_t)hip_stream));
+    else LLSA_TRY(launch_attn_fwd_generic(p, t, Q, O, LSE, (hipStream_t)hip_stream));
     return LLSA_OK;
 }
 

@@ -64,4 +64,7 @@ hipError_t launch_dkv_generic(const Plan &p, const LevelTable &t, int l, const v
                               const float *LSE, const float *D, void *ws, void *dK, void *dV, hipStream_t s);
 hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
 
+// ---- bf16 MFMA kernels (B = 16, d = 64 or 128) ----
+hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);
+
 }  // namespace llsa

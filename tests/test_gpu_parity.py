@@ -71,6 +71,10 @@ def test_config1_n4096_bf16_all_heads():
     dict(name="B3_d128", batch=1, heads=3, d=128, N=729, B=3, K=2, L=4, dtype="bf16", kind="gaussian"),
     # top level with one token
     dict(name="one_top_token", batch=1, heads=1, d=16, N=64, B=4, K=2, L=3, dtype="f32", kind="gaussian"),
+    # d = 128 on the MFMA path; odd number of key blocks with a ragged coarsest level (40 tokens: 16 + 16 + 8)
+    dict(name="d128_B16", batch=1, heads=2, d=128, N=4096, B=16, K=8, L=2, dtype="bf16", kind="smooth"),
+    dict(name="ragged_top", batch=1, heads=3, d=64, N=640, B=16, K=4, L=1, dtype="bf16", kind="gaussian"),
+    dict(name="ragged_top_d128", batch=2, heads=1, d=128, N=16 * 16 * 3, B=16, K=2, L=2, dtype="bf16", kind="gaussian"),
     # larger K sweep value
     dict(name="K16", batch=1, heads=2, d=64, N=4096, B=16, K=16, L=2, dtype="bf16", kind="smooth"),
 ])
