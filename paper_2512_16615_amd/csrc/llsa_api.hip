@@ -103,10 +103,17 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
         p.dKacc_off[l] = ws; ws = align_up(ws + bytes);
         p.dVacc_off[l] = ws; ws = align_up(ws + bytes);
     }
+    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && d.B == 16 && (d.d == 64 || d.d == 128);
     p.part_off = ws;
     p.part_bytes = 0;
+    if (p.fast)
+        for (int l = 1; l <= p.Le; ++l) {                  // split slabs of the key-major coarse-level kernels
+            const size_t slab = (size_t)p.bh * ((p.n[l] + 15) / 16) * 16 * p.d * sizeof(float);
+            const size_t need = 2 * slab * dkv_splits(p, l);
+            if (need > p.part_bytes) p.part_bytes = need;
+        }
+    ws = align_up(ws + p.part_bytes);
     p.ws_bwd = ws;
-    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && d.B == 16 && (d.d == 64 || d.d == 128);
     return LLSA_OK;
 }
 
@@ -280,19 +287,25 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     LevelTable t = make_level_table(p, K, V, indices, workspace);
     {
         StageScope sc(kDq, call, s);
-        LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
+        if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, dO, LSE, D, dQ, s));
+        else LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
     }
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
     {
         StageScope sc(kDkvCoarse, call, s);
-        for (int l = p.Le; l >= 1; --l) LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+        for (int l = p.Le; l >= 1; --l) {
+            if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+            else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+        }
     }
     {
         StageScope sc(kUnpool, call, s);
-        for (int l = p.Le; l >= 2; --l) LLSA_TRY(launch_unpool(p, l, workspace, s));
+        if (!p.fast)                                        // the MFMA path folds this into its slab reduction
+            for (int l = p.Le; l >= 2; --l) LLSA_TRY(launch_unpool(p, l, workspace, s));
     }
     StageScope sc(kDkvFine, call, s);
-    LLSA_TRY(launch_dkv_generic(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
+    if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
+    else LLSA_TRY(launch_dkv_generic(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
     return LLSA_OK;
 }
 

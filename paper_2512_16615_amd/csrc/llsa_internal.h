@@ -66,5 +66,12 @@ hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
 
 // ---- bf16 MFMA kernels (B = 16, d = 64 or 128) ----
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);
+hipError_t launch_dq_mfma(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
+                          const float *D, void *dQ, hipStream_t s);
+// key-major dK/dV of level l; levels >= 1 also fold their split slabs and the level above into the
+// level's fp32 gradient buffer, so they must be launched from the coarsest level down
+hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO, const float *LSE,
+                           const float *D, void *ws, void *dK, void *dV, hipStream_t s);
+int dkv_splits(const Plan &p, int l);    // workgroups sharing one key block's query list at level l
 
 }  // namespace llsa
