@@ -1,162 +1,31 @@
-// Backward of the gathered-list attention on bf16 MFMA (B = 16, d = 64 or 128), Sec. 4.3:
-//   dq_mfma_kernel   query-major, same list walk as the forward (P recomputed from the saved logsumexp);
-//   dkv_mfma_kernel  key-major over the transposed lists of Alg. 2 (or over every query at the coarsest
-//                    enriched level), no mask and no floating-point atomics.
-// With P = exp(z - LSE), dP = dO V^T, dS = P o (dP - D), D = rowsum(dO o O):
-//   dQ = scale dS K,   dK = scale dS^T Q,   dV = P^T dO.
-// Both kernels compute the score tiles in the orientation whose accumulator layout (4 contraction slots
-// of one output column per lane) is directly the B operand of the next product, and read the operand
-// that must be contracted over its row index through the transposing LDS read.
-#include "mfma_common.h"
-
-namespace llsa {
-
-constexpr float kLog2e = 1.4426950408889634f;
-
-// --------------------------------------------------------------------------------------------------- dQ
-// One wave per fine query block.  Per tile of two 16-token key blocks:
-//   S^T = K Q^T, dP^T = V dO^T  (lane: 4 keys x 1 query)  ->  dS^T  ->  dQ^T += K^T dS^T.
-// K tiles are staged in the wave's LDS region and read twice (row-wise for S^T, transposed for dQ^T);
-// V rows go straight from global memory into the A operand.
-template <int D>
-__global__ void __launch_bounds__(256) dq_mfma_kernel(LevelTable t, const uint16_t *__restrict__ Q,
-                                                       const uint16_t *__restrict__ dO, const float *__restrict__ LSE,
-                                                       const float *__restrict__ Dsum, uint16_t *__restrict__ dQ,
-                                                       int64_t N, int64_t total_blocks) {
-    constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, VCH = D / 16, PARTS = D / 8, KPU = 64 / PARTS;
-    __shared__ __attribute__((aligned(16))) char klds[4][32 * STRIDE];
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t fb = (int64_t)blockIdx.x * 4 + wave;
-    if (fb >= total_blocks) return;       // no workgroup barrier below
-    const int64_t nblk = N >> 4, bh = fb / nblk, blk = fb % nblk;
-    const int i16 = lane & 15, g = lane >> 4;
-    char *my = klds[wave];
-
-    const int64_t qrow = bh * N + blk * 16 + i16;
-    bf16x8 qop[KS], gop[KS];
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        qop[s] = ld_bf16x8(Q + qrow * D + g * 8 + 32 * s);
-        gop[s] = ld_bf16x8(dO + qrow * D + g * 8 + 32 * s);
-    }
-    const float lse2 = LSE[qrow] * kLog2e, delta = Dsum[qrow];
-    const float sc2 = t.scale * kLog2e;
-    f32x4 acc[NT];
-#pragma unroll
-    for (int n = 0; n < NT; ++n) acc[n] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    BlockWalker walk(t, bh, blk);
-    KeyBlock kb[2];
-    bf16x8 vop[2][KS];
-    u32x4 kreg[VCH];
-
-    auto load_tile = [&]() {
-        kb[0] = walk.next(D);
-        kb[1] = walk.next(D);
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const KeyBlock &b = kb[h].cnt > 0 ? kb[h] : kb[0];
-            const uint16_t *vr = b.V + min(i16, b.cnt - 1) * D + g * 8;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) vop[h][s] = ld_bf16x8(vr + 32 * s);
-        }
-#pragma unroll
-        for (int u = 0; u < VCH; ++u) {
-            const int key = lane / PARTS + KPU * u, part = lane % PARTS, h = (KPU * u) >> 4;
-            const KeyBlock &b = kb[h].cnt > 0 ? kb[h] : kb[0];
-            kreg[u] = *reinterpret_cast<const u32x4 *>(b.K + min(key & 15, b.cnt - 1) * D + part * 8);
-        }
-    };
-
-    load_tile();
-    while (true) {
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int u = 0; u < VCH; ++u) {
-            const int key = lane / PARTS + KPU * u, part = lane % PARTS;
-            *reinterpret_cast<u32x4 *>(my + key * STRIDE + part * 16) = kreg[u];
-        }
-        __builtin_amdgcn_wave_barrier();
-
-        f32x4 s[2], dp[2];
-        float bias2[2];
-        int cnt[2];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-            dp[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const char *krow = my + (h * 16 + i16) * STRIDE + g * 16;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                s[h] = mfma16(*reinterpret_cast<const bf16x8 *>(krow + ks * 64), qop[ks], s[h]);
-                dp[h] = mfma16(vop[h][ks], gop[ks], dp[h]);
-            }
-            bias2[h] = kb[h].bias2;
-            cnt[h] = kb[h].cnt;
-        }
-        const bool more = !walk.done();
-        if (more) load_tile();             // the K tile in LDS stays valid until the next iteration's stores
-
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float p = (4 * g + r < cnt[h]) ? __builtin_amdgcn_exp2f(fmaf(s[h][r], sc2, bias2[h]) - lse2) : 0.f;
-                s[h][r] = p * (dp[h][r] - delta);
-            }
-        const bf16x8 dsop = pack8(s[0], s[1]);
-        const char *base = my + (4 * g + (i16 >> 2)) * STRIDE + (i16 & 3) * 8;
-#pragma unroll
-        for (int n = 0; n < NT; ++n)
-            acc[n] = mfma16(lds_tr_pair(base + n * 32, base + 16 * STRIDE + n * 32), dsop, acc[n]);
-        if (!more) break;
-    }
-
-    uint16_t *orow = dQ + qrow * D + 4 * g;
-#pragma unroll
-    for (int n = 0; n < NT; ++n) {
-        u32x2 w;
-        w[0] = pack_bf16(acc[n][0] * t.scale, acc[n][1] * t.scale);
-        w[1] = pack_bf16(acc[n][2] * t.scale, acc[n][3] * t.scale);
-        *reinterpret_cast<u32x2 *>(orow + n * 16) = w;
-    }
-}
-
-hipError_t launch_dq_mfma(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
-                          const float *D, void *dQ, hipStream_t s) {
-    const int64_t total = (int64_t)p.bh * (p.N / 16);
-    dim3 grid((unsigned)((total + 3) / 4));
-    if (p.d == 64)
-        dq_mfma_kernel<64><<<grid, 256, 0, s>>>(t, (const uint16_t *)Q, (const uint16_t *)dO, LSE, D, (uint16_t *)dQ,
-                                                p.N, total);
-    else
-        dq_mfma_kernel<128><<<grid, 256, 0, s>>>(t, (const uint16_t *)Q, (const uint16_t *)dO, LSE, D, (uint16_t *)dQ,
-                                                 p.N, total);
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------------ dK, dV
+// dK, dV of the gathered-list attention on bf16 MFMA (B = 16, d = 64 or 128), Sec. 4.3: key-major over
+// the transposed lists of Alg. 2 (or over every query at the coarsest enriched level), with no mask and
+// no floating-point atomics.
+// With P = exp(z - LSE), dP = dO V^T, dS = P o (dP - D):  dK = scale dS^T Q,  dV = P^T dO.
+//
 // One workgroup (4 waves) per (key block of 16 level-l tokens, split).  The queries that attend to the
-// block are the fine queries under the level-l query blocks listed for it (Alg. 2's key-major lists),
-// walked in groups of 16 consecutive queries; a tile is two groups.  The tiles of the workgroup's share
-// are dealt round-robin to its waves.  Per tile:
+// block are the fine queries under the level-l query blocks listed for it, walked in groups of 16
+// consecutive queries; a tile is two groups.  The tiles of the workgroup's share are dealt round-robin
+// to its waves.  Per tile:
 //   S = Q K^T, dP = dO V^T   (lane: 4 queries x 1 key)  ->  P, dS  ->
 //   dV^T += dO^T P,  dK^T += Q^T dS   (A = the Q / dO tile read transposed from LDS, B = P / dS).
 // The four waves' accumulators are summed through LDS in wave order, so the result does not depend on
 // timing.  Level 0 (no split) finishes in place: adds the parent token's share (adjoint of mean pooling)
 // and rounds once; coarser levels write fp32 partial sums, one slab per split, that a second kernel
 // adds up in split order.
+#include "mfma_common.h"
+
+namespace llsa {
+
 struct DkvArgs {
     const uint16_t *Q, *dO, *Kl, *Vl;     // Kl, Vl: the level's keys / values [bh, n_l, D]
     const float *LSE, *Dsum;
     const int32_t *C, *Iq;                // key-major lists (unused when dense)
-    float *partK, *partV;                 // [splits][bh * n_l * D] fp32 (levels >= 1)
+    float *partK, *partV;                 // [splits][slab] fp32 (levels >= 1)
     const float *parK, *parV;             // level-1 totals [bh, n_1, D] fp32 or null (level 0)
     uint16_t *dK, *dV;                    // level-0 outputs
-    int64_t N, n_l, rows;                 // rows = key blocks of this level per head that have lists
-    int64_t span16;                       // 16-query groups per listed query block = B^(l+1) / 16
+    int64_t N, n_l, rows, slab;           // rows = key blocks of this level per head that have lists
+    int span_shift;                       // log2 of the 16-query groups per listed query block = 4 * level
     int Kl_cnt, level, dense, splits;
     float sc2, bias2, scale;
 };
@@ -196,38 +65,41 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
         const int32_t *Crow = a.C + bh * (a.rows + 1) + j;
         const int32_t beg = Crow[0], end = Crow[1];
         lst = a.Iq + bh * a.rows * a.Kl_cnt + beg;
-        groups = (int64_t)(end - beg) * a.span16;
+        groups = (int64_t)(end - beg) << a.span_shift;
     }
     const int64_t tiles = (groups + 1) >> 1;
     const int64_t t_beg = tiles * split / a.splits, t_end = tiles * (split + 1) / a.splits;
+    const int64_t span_mask = ((int64_t)1 << a.span_shift) - 1;
 
     f32x4 accK[NT], accV[NT];
 #pragma unroll
     for (int n = 0; n < NT; ++n) { accK[n] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[n] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 
+    int voff[VCH];
+#pragma unroll
+    for (int u = 0; u < VCH; ++u) voff[u] = (((lane / PARTS + KPU * u) & 15) * D + (lane % PARTS) * 8) * 2;
+
     u32x4 qreg[VCH], greg[VCH];
-    f32x4 lse2[2], del[2];
-    int valid[2];
-    auto group_row = [&](int64_t gi) -> int64_t {           // first fine query row (flat) of group gi
-        const int64_t q0 = a.dense ? gi * 16 : ((int64_t)lst[gi / a.span16] * a.span16 + gi % a.span16) * 16;
-        return bh * a.N + q0;
-    };
+    f32x4 lse[2], del[2];
+    int valid1;                                             // does the tile have its second group?
     auto load_tile = [&](int64_t tile) {
-        int64_t row0[2];
+        const char *qp[2], *gp[2];
+        valid1 = 2 * tile + 1 < groups;
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            const int64_t gi = 2 * tile + h;
-            valid[h] = gi < groups;
-            row0[h] = group_row(valid[h] ? gi : 2 * tile);
-            lse2[h] = *reinterpret_cast<const f32x4 *>(a.LSE + row0[h] + 4 * g);
-            del[h] = *reinterpret_cast<const f32x4 *>(a.Dsum + row0[h] + 4 * g);
+            const int64_t gi = (h == 0 || valid1) ? 2 * tile + h : 2 * tile;   // an absent group re-reads the first
+            const int64_t q0 = a.dense ? gi * 16 : (((int64_t)lst[gi >> a.span_shift] << a.span_shift) + (gi & span_mask)) * 16;
+            const int64_t row0 = bh * a.N + q0;
+            lse[h] = *reinterpret_cast<const f32x4 *>(a.LSE + row0 + 4 * g);
+            del[h] = *reinterpret_cast<const f32x4 *>(a.Dsum + row0 + 4 * g);
+            qp[h] = reinterpret_cast<const char *>(a.Q + row0 * D);
+            gp[h] = reinterpret_cast<const char *>(a.dO + row0 * D);
         }
 #pragma unroll
         for (int u = 0; u < VCH; ++u) {
-            const int q = lane / PARTS + KPU * u, part = lane % PARTS, h = (KPU * u) >> 4;
-            const int64_t off = (row0[h] + (q & 15)) * D + part * 8;
-            qreg[u] = *reinterpret_cast<const u32x4 *>(a.Q + off);
-            greg[u] = *reinterpret_cast<const u32x4 *>(a.dO + off);
+            const int h = (KPU * u) >> 4;
+            qreg[u] = *reinterpret_cast<const u32x4 *>(qp[h] + voff[u]);
+            greg[u] = *reinterpret_cast<const u32x4 *>(gp[h] + voff[u]);
         }
     };
 
@@ -243,8 +115,7 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
         }
         __builtin_amdgcn_wave_barrier();
 
-        f32x4 s[2], dp[2], l2[2], dl[2];
-        int vld[2];
+        f32x4 s[2], dp[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -255,8 +126,9 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
                 s[h] = mfma16(*reinterpret_cast<const bf16x8 *>(qrow + ks * 64), kop[ks], s[h]);
                 dp[h] = mfma16(*reinterpret_cast<const bf16x8 *>(grow + ks * 64), vop[ks], dp[h]);
             }
-            l2[h] = lse2[h]; dl[h] = del[h]; vld[h] = valid[h];
         }
+        const f32x4 l2[2] = {lse[0], lse[1]}, dl[2] = {del[0], del[1]};
+        const int v1 = valid1;
         const int64_t next = tile + 4;
         if (next < t_end) load_tile(next);
 
@@ -264,10 +136,14 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
         for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float p = vld[h] ? __builtin_amdgcn_exp2f(fmaf(s[h][r], a.sc2, a.bias2) - l2[h][r] * kLog2e) : 0.f;
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[h][r], a.sc2, fmaf(l2[h][r], -kLog2e, a.bias2)));
                 s[h][r] = p;
                 dp[h][r] = p * (dp[h][r] - dl[h][r]);
             }
+        if (!v1) {                                          // the list ends with a single group
+            s[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+            dp[1] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
         const bf16x8 pop = pack8(s[0], s[1]), dsop = pack8(dp[0], dp[1]);
         const int boff = (4 * g + (i16 >> 2)) * STRIDE + (i16 & 3) * 8;
 #pragma unroll
@@ -307,7 +183,7 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) sum[r] *= a.scale;
         if (a.level > 0) {
-            float *dst = (isV ? a.partV : a.partK) + (int64_t)split * (gridDim.x / a.splits) * 16 * D;
+            float *dst = (isV ? a.partV : a.partK) + (int64_t)split * a.slab;
             *reinterpret_cast<f32x4 *>(dst + tok * D + col) = sum;
         } else {
             const float *par = isV ? a.parV : a.parK;
@@ -326,21 +202,25 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
 
 // Adds the split slabs of one coarse level in split order and, if there is a coarser level above it,
 // that level's share (adjoint of mean pooling, 1/16 of the parent token): dst[t] = sum_s part[s][t]
-// (+ up[t / 16] / 16).  dst is the level's fp32 gradient buffer.
+// (+ up[t / 16] / 16).  dst is the level's fp32 gradient buffer.  One thread per 4 consecutive floats.
 __global__ void __launch_bounds__(256) dkv_reduce_kernel(const float *partK, const float *partV, float *dstK,
                                                           float *dstV, const float *upK, const float *upV,
-                                                          int64_t total, int64_t slab, int splits, int d) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= total) return;
-    float k = 0.f, v = 0.f;
-    for (int s = 0; s < splits; ++s) { k += partK[s * slab + i]; v += partV[s * slab + i]; }
+                                                          int64_t total4, int64_t slab, int splits, int d) {
+    const int64_t i4 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i4 >= total4) return;
+    const int64_t i = i4 * 4;
+    f32x4 k = {0.f, 0.f, 0.f, 0.f}, v = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < splits; ++s) {
+        k += *reinterpret_cast<const f32x4 *>(partK + s * slab + i);
+        v += *reinterpret_cast<const f32x4 *>(partV + s * slab + i);
+    }
     if (upK) {
         const int64_t tok = i / d, c = i % d;
-        k += upK[(tok >> 4) * d + c] * 0.0625f;
-        v += upV[(tok >> 4) * d + c] * 0.0625f;
+        k += *reinterpret_cast<const f32x4 *>(upK + (tok >> 4) * d + c) * 0.0625f;
+        v += *reinterpret_cast<const f32x4 *>(upV + (tok >> 4) * d + c) * 0.0625f;
     }
-    dstK[i] = k;
-    dstV[i] = v;
+    *reinterpret_cast<f32x4 *>(dstK + i) = k;
+    *reinterpret_cast<f32x4 *>(dstV + i) = v;
 }
 
 int dkv_splits(const Plan &p, int l) {
@@ -351,7 +231,7 @@ int dkv_splits(const Plan &p, int l) {
     int64_t s = (4096 + key_blocks - 1) / key_blocks;
     if (s > tiles_per_block / 8) s = tiles_per_block / 8;
     if (s < 1) s = 1;
-    if (s > 256) s = 256;
+    if (s > 64) s = 64;
     return (int)s;
 }
 
@@ -359,6 +239,7 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
                            const float *D, void *ws, void *dK, void *dV, hipStream_t s) {
     char *w = static_cast<char *>(ws);
     DkvArgs a;
+    const int64_t key_blocks = (int64_t)p.bh * ((p.n[l] + 15) / 16);
     a.Q = (const uint16_t *)Q; a.dO = (const uint16_t *)dO;
     a.Kl = (const uint16_t *)t.K[l]; a.Vl = (const uint16_t *)t.V[l];
     a.LSE = LSE; a.Dsum = D;
@@ -366,31 +247,31 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
     a.C = a.dense ? nullptr : (const int32_t *)(w + p.C_off[l]);
     a.Iq = a.dense ? nullptr : (const int32_t *)(w + p.Iq_off[l]);
     a.splits = dkv_splits(p, l);
+    a.slab = key_blocks * 16 * p.d;
     a.partK = (float *)(w + p.part_off);
-    a.partV = a.partK + (size_t)a.splits * p.bh * ((p.n[l] + 15) / 16) * 16 * p.d;
+    a.partV = a.partK + (size_t)a.splits * a.slab;
     const bool has_parent = (l == 0 && p.Le >= 1);
     a.parK = has_parent ? (const float *)(w + p.dKacc_off[1]) : nullptr;
     a.parV = has_parent ? (const float *)(w + p.dVacc_off[1]) : nullptr;
     a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
     a.N = p.N; a.n_l = p.n[l];
     a.rows = a.dense ? 0 : p.n[l + 1];
-    a.span16 = a.dense ? 1 : t.Bpow[l + 1] / 16;
+    a.span_shift = a.dense ? 0 : 4 * l;
     a.Kl_cnt = a.dense ? 0 : p.Kl[l];
     a.level = l;
     a.sc2 = p.scale * kLog2e; a.bias2 = t.bias[l] * kLog2e; a.scale = p.scale;
-    const int64_t key_blocks = (int64_t)p.bh * ((p.n[l] + 15) / 16);
     dim3 grid((unsigned)(key_blocks * a.splits));
     if (p.d == 64) dkv_mfma_kernel<64><<<grid, 256, 0, s>>>(a);
     else dkv_mfma_kernel<128><<<grid, 256, 0, s>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || l == 0) return e;
     // fold the slabs (and the level above) into this level's fp32 gradient
-    const int64_t total = (int64_t)p.bh * p.n[l] * p.d;
+    const int64_t total4 = (int64_t)p.bh * p.n[l] * p.d / 4;
     const bool has_up = l < p.Le;
-    dkv_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(
+    dkv_reduce_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(
         a.partK, a.partV, (float *)(w + p.dKacc_off[l]), (float *)(w + p.dVacc_off[l]),
         has_up ? (const float *)(w + p.dKacc_off[l + 1]) : nullptr, has_up ? (const float *)(w + p.dVacc_off[l + 1]) : nullptr,
-        total, (int64_t)key_blocks * 16 * p.d, a.splits, p.d);
+        total4, a.slab, a.splits, p.d);
     return hipGetLastError();
 }
 

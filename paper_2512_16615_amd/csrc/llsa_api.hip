@@ -19,7 +19,7 @@ LevelTable make_level_table(const Plan &p, const void *K0, const void *V0, const
     const char *w = static_cast<const char *>(workspace);
     const char *idx = reinterpret_cast<const char *>(indices);
     int64_t bp = 1;
-    int pos = 0;
+    int pos = 0, bpos = 0;
     for (int l = 0; l <= p.L; ++l) {
         t.K[l] = (l == 0) ? K0 : (const void *)(w + p.pyr_off[1][l]);
         t.V[l] = (l == 0) ? V0 : (const void *)(w + p.pyr_off[2][l]);
@@ -32,12 +32,15 @@ LevelTable make_level_table(const Plan &p, const void *K0, const void *V0, const
         if (l <= p.Le) {
             t.seg[l] = pos;
             pos += (l < p.L) ? p.Kl[l] * p.B : (int)p.n[l];
+            t.bseg[l] = bpos;
+            bpos += (l < p.L) ? p.Kl[l] : (int)((p.n[l] + 15) / 16);
         }
         bp *= p.B;
     }
     t.Bpow[p.L + 1] = bp;
     t.nlev = p.Le + 1;
     t.seg[t.nlev] = pos;
+    t.bseg[t.nlev] = bpos;
     t.L = p.L;
     t.B = p.B;
     t.d = p.d;
@@ -103,7 +106,8 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
         p.dKacc_off[l] = ws; ws = align_up(ws + bytes);
         p.dVacc_off[l] = ws; ws = align_up(ws + bytes);
     }
-    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && d.B == 16 && (d.d == 64 || d.d == 128);
+    // MFMA kernels: bf16, B = 16, d = 64 / 128, and whole workgroups of 4 query blocks per head
+    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && d.B == 16 && (d.d == 64 || d.d == 128) && d.N % 64 == 0;
     p.part_off = ws;
     p.part_bytes = 0;
     if (p.fast)
@@ -275,7 +279,7 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         LLSA_TRY(launch_pool(p, Q, K, V, workspace, false, s));
     }
     float *D = reinterpret_cast<float *>(w + p.D_off);
-    {
+    if (!p.fast) {                                          // the MFMA dQ kernel produces D itself
         StageScope sc(kBwdPre, call, s);
         LLSA_TRY(launch_bwd_pre(p, O, dO, D, s));
     }
@@ -287,7 +291,7 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     LevelTable t = make_level_table(p, K, V, indices, workspace);
     {
         StageScope sc(kDq, call, s);
-        if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, dO, LSE, D, dQ, s));
+        if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, O, dO, LSE, D, dQ, s));
         else LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
     }
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share

@@ -41,6 +41,7 @@ struct LevelTable {
     int64_t Bpow[kMaxL + 2];        // B^l
     int Kl[kMaxL + 1];
     int seg[kMaxL + 2];             // list position where level l starts; seg[nlev] = list length
+    int bseg[kMaxL + 2];            // same in units of 16-token key blocks (used when B = 16)
     float bias[kMaxL + 1];          // l * ln B (or 0)
     int nlev;                       // levels in the list = Le + 1
     int L, B, d;
@@ -66,8 +67,9 @@ hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
 
 // ---- bf16 MFMA kernels (B = 16, d = 64 or 128) ----
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);
-hipError_t launch_dq_mfma(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
-                          const float *D, void *dQ, hipStream_t s);
+// also writes D = rowsum(dO * O) for the key-major kernels that follow
+hipError_t launch_dq_mfma(const Plan &p, const LevelTable &t, const void *Q, const void *O, const void *dO,
+                          const float *LSE, float *D, void *dQ, hipStream_t s);
 // key-major dK/dV of level l; levels >= 1 also fold their split slabs and the level above into the
 // level's fp32 gradient buffer, so they must be launched from the coarsest level down
 hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO, const float *LSE,

@@ -1,5 +1,5 @@
 // Device helpers shared by the bf16 MFMA kernels (gfx950): vector types, the 16x16x32 bf16 MFMA, the LDS
-// transpose read and the walk over the 16-token key blocks of a query block's gathered list.
+// transpose read, cross-row reductions and the table of 16-token key blocks of a query block's list.
 //
 // Register layouts of v_mfma_f32_16x16x32_bf16 (lane = 16*g + i, g = 0..3, i = 0..15):
 //   A (16 x 32): lane holds row i,    contraction slots 8g .. 8g+7
@@ -7,20 +7,24 @@
 //   D (16 x 16): lane holds column i, rows 4g .. 4g+3
 // ds_read_b64_tr_b16 (per block of 16 lanes, lane r supplies the address of 4 consecutive 16-bit
 // values): output lane i, element e = element (i % 4) of the chunk addressed by lane 4e + i / 4.
+// v_permlane16_swap / v_permlane32_swap with both operands equal to x return {x[l], x[l ^ 16]} resp.
+// {x[l], x[l ^ 32]} (in some order) in every lane l.
 #pragma once
 #include "llsa_internal.h"
 
 namespace llsa {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define LLSA_LDS __attribute__((address_space(3)))
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
@@ -28,18 +32,19 @@ __device__ __forceinline__ f32x4 mfma16(bf16x8 a, bf16x8 b, f32x4 c) {
 
 __device__ __forceinline__ bf16x8 ld_bf16x8(const void *p) { return *reinterpret_cast<const bf16x8 *>(p); }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs)
-__device__ __forceinline__ uint32_t bf16_bits(float f) {
-    const uint32_t u = __float_as_uint(f);
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+// two fp32 -> packed bf16 (round to nearest even; one v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    union { bf16x2 v; uint32_t u; } r;
+    r.v[0] = (__bf16)lo;
+    r.v[1] = (__bf16)hi;
+    return r.u;
 }
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) { return bf16_bits(lo) | (bf16_bits(hi) << 16); }
 
 __device__ __forceinline__ bf16x8 pack8(const f32x4 &a, const f32x4 &b) {
-    union { uint32_t u[4]; bf16x8 v; } r;
-    r.u[0] = pack_bf16(a[0], a[1]); r.u[1] = pack_bf16(a[2], a[3]);
-    r.u[2] = pack_bf16(b[0], b[1]); r.u[3] = pack_bf16(b[2], b[3]);
-    return r.v;
+    bf16x8 r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { r[i] = (__bf16)a[i]; r[4 + i] = (__bf16)b[i]; }
+    return r;
 }
 
 // Two transposing LDS reads glued into one 8-slot MFMA operand.
@@ -48,6 +53,20 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const char *lo, const char *hi) {
     r.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LLSA_LDS s16x4 *)(lo));
     r.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LLSA_LDS s16x4 *)(hi));
     return r.v;
+}
+
+// All-reduce over the four lanes {i, i+16, i+32, i+48} (the four row groups of one MFMA column).
+__device__ __forceinline__ float rows_max(float x) {
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float rows_sum(float x) {
+    auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    const float y = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(y), __float_as_uint(y), false, false);
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
 // arr[idx] for a small kernel-argument array without dynamic indexing (which would spill the table to
@@ -60,48 +79,59 @@ __device__ __forceinline__ T pick(const T (&arr)[n], int idx) {
     return v;
 }
 
-// One 16-token key block of a gathered list.
-struct KeyBlock {
-    const uint16_t *K, *V;   // first row of the block in its level's key / value tensor
-    float bias2;             // log2 of the level's token weight
-    int cnt;                 // valid tokens (16, or fewer in the last block of the coarsest level; 0 = no block)
-};
+// Workgroup id -> work item so that the workgroups one XCD receives (ids congruent modulo 8) cover a
+// contiguous range of work items: neighbouring query blocks gather overlapping keys, which then stay in
+// that XCD's L2.
+__device__ __forceinline__ int64_t xcd_contiguous(int64_t w, int64_t total) {
+    const int64_t per = total >> 3;
+    return (w < per * 8) ? (w & 7) * per + (w >> 3) : w;
+}
 
-// Walks the key blocks of fine query block `blk` of head `bh` in list order (Alg. 1, enrichment loop),
-// for B = 16.  Everything here is wave-uniform.
-struct BlockWalker {
-    const LevelTable &t;
-    int64_t bh, blk;
-    int l, k, nk;
-    __device__ BlockWalker(const LevelTable &tab, int64_t bh_, int64_t blk_) : t(tab), bh(bh_), blk(blk_), l(0), k(0) {
-        nk = count(0);
-    }
-    __device__ int count(int lev) const {
-        if (lev >= t.nlev) return 0;
-        return lev < t.L ? pick(t.Kl, lev) : (int)((pick(t.n, lev) + 15) >> 4);
-    }
-    __device__ bool done() const { return l >= t.nlev; }
-    // d = head dimension; an exhausted walker returns cnt = 0 and null pointers
-    __device__ KeyBlock next(int d) {
-        KeyBlock b;
-        if (done()) { b.K = b.V = nullptr; b.bias2 = 0.f; b.cnt = 0; return b; }
-        const int64_t n_l = pick(t.n, l);
-        int64_t tok0;
-        if (l < t.L) {
-            const int64_t row = blk / pick(t.Bpow, l);
-            const int kl = pick(t.Kl, l);
-            tok0 = (int64_t)pick(t.I, l)[(bh * pick(t.rows, l) + row) * kl + k] * 16;
-            b.cnt = 16;
-        } else {
-            tok0 = k * 16;
-            b.cnt = min(16, (int)n_l - k * 16);
+// The 16-token key blocks of one fine query block's list (Alg. 1, enrichment loop; B = 16), 64 at a time:
+// lane j of the wave describes block 64 * chunk + j.  The main loops fetch a block's fields with
+// v_readlane (block numbers are wave-uniform), which keeps the per-tile scalar work small.
+struct BlockTable {
+    uint64_t kptr, vptr;     // address of the block's first key / value row
+    float bias2;             // log2 of the level's token weight
+    int cnt;                 // valid rows: 16, fewer in the last block of a ragged coarsest level, 0 past the end
+
+    __device__ __forceinline__ void fill(const LevelTable &t, int64_t bh, int64_t blk, int chunk, int lane, int d) {
+        const int jb = chunk * 64 + lane;
+        kptr = vptr = 0;
+        bias2 = 0.f;
+        cnt = 0;
+        for (int l = 0; l < t.nlev; ++l) {                       // wave-uniform loop over the levels in the list
+            const int b0 = pick(t.bseg, l), b1 = pick(t.bseg, l + 1);
+            const int64_t n_l = pick(t.n, l);
+            const char *Kb = static_cast<const char *>(pick(t.K, l)), *Vb = static_cast<const char *>(pick(t.V, l));
+            if (jb >= b0 && jb < b1) {
+                const int k = jb - b0;
+                int64_t tok0;
+                if (l < t.L) {
+                    const int64_t row = blk >> (4 * l);
+                    tok0 = (int64_t)pick(t.I, l)[(bh * pick(t.rows, l) + row) * pick(t.Kl, l) + k] * 16;
+                    cnt = 16;
+                } else {
+                    tok0 = (int64_t)k * 16;
+                    cnt = min(16, (int)(n_l - tok0));
+                }
+                const int64_t off = (bh * n_l + tok0) * d * 2;
+                kptr = reinterpret_cast<uint64_t>(Kb + off);
+                vptr = reinterpret_cast<uint64_t>(Vb + off);
+                bias2 = pick(t.bias, l) * kLog2e;
+            }
         }
-        const int64_t off = (bh * n_l + tok0) * d;
-        b.K = static_cast<const uint16_t *>(pick(t.K, l)) + off;
-        b.V = static_cast<const uint16_t *>(pick(t.V, l)) + off;
-        b.bias2 = pick(t.bias, l) * 1.4426950408889634f;
-        if (++k == nk) { ++l; k = 0; nk = count(l); }
-        return b;
+    }
+    static __device__ __forceinline__ const char *rl_ptr(uint64_t v, int j) {
+        const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, j);
+        const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), j);
+        return reinterpret_cast<const char *>(((uint64_t)hi << 32) | lo);
+    }
+    __device__ __forceinline__ const char *K(int j) const { return rl_ptr(kptr, j); }
+    __device__ __forceinline__ const char *V(int j) const { return rl_ptr(vptr, j); }
+    __device__ __forceinline__ int count(int j) const { return __builtin_amdgcn_readlane(cnt, j); }
+    __device__ __forceinline__ float bias(int j) const {
+        return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(bias2), j));
     }
 };
 
