@@ -67,6 +67,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="index into BASELINE.json configs (default: headline)")
     ap.add_argument("--kind", default=None, help="override the input kind: smooth | gaussian")
+    ap.add_argument("--Le", type=int, default=None, help="override the number of enrichment levels (default: L)")
     ap.add_argument("--stage", default="auto", help="stage whose kernel is bracketed by HIP events in the timed region")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle leg")
     ap.add_argument("--all-stages", action="store_true", help="after the timed region, one more pass timing every stage")
@@ -103,7 +104,7 @@ def main():
     print(f"[bench] inputs ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 
     plan = llsa.Plan(cfg["batch"], cfg["heads"], cfg["N"], cfg["d"], cfg["B"], cfg["K"], cfg["L"],
-                     dtype=llsa.BF16 if bf16 else llsa.F32, kernel_path=1 if args.force_generic else 0)
+                     Le=args.Le, dtype=llsa.BF16 if bf16 else llsa.F32, kernel_path=1 if args.force_generic else 0)
     ws = plan.alloc_workspace(True)
     idx = plan.alloc_indices()
     Q, K, V, dO = dev["Q"], dev["K"], dev["V"], dev["dO"]

@@ -15,7 +15,7 @@
 namespace llsa {
 
 template <int D>
-__global__ void __launch_bounds__(256) attn_fwd_mfma_kernel(LevelTable t, const uint16_t *__restrict__ Q,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2))) attn_fwd_mfma_kernel(LevelTable t, const uint16_t *__restrict__ Q,
                                                              uint16_t *__restrict__ O, float *__restrict__ LSE,
                                                              int64_t N, int64_t total_wgs) {
     constexpr int KS = D / 32;            // MFMA steps over d for S^T
@@ -48,7 +48,7 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_kernel(LevelTable t, const 
     const int nb = t.bseg[t.nlev];                                   // key blocks in the list
 
     BlockTable tab;
-    tab.fill(t, bh, blk, 0, lane, D);
+    tab.fill(t, bh, blk, 0, 0, lane, D);
 
     // per-lane byte offsets inside a block (row-wise operand load / 16-byte staging chunks)
     const int koff = (i16 * D + g * 8) * 2;
@@ -62,7 +62,7 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_kernel(LevelTable t, const 
     int cnt[2];
 
     auto load_tile = [&](int j0) {                                   // blocks j0 and j0 + 1 (j0 even)
-        if (j0 > 0 && (j0 & 63) == 0) tab.fill(t, bh, blk, j0 >> 6, lane, D);
+        if (j0 > 0 && (j0 & 63) == 0) tab.fill(t, bh, blk, 0, j0 >> 6, lane, D);
         const char *kp[2], *vp[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -167,6 +167,7 @@ __global__ void __launch_bounds__(256) attn_fwd_mfma_kernel(LevelTable t, const 
 
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                 hipStream_t s) {
+    if (p.d == 64 && p.N % 256 == 0) return launch_attn_fwd_shared(p, t, Q, O, LSE, s);
     const int64_t wgs = (int64_t)p.bh * (p.N / 64);                  // 4 query blocks per workgroup
     dim3 grid((unsigned)wgs);
     if (p.d == 64)

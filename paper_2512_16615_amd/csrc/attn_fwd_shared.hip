@@ -1,0 +1,258 @@
+// Attention forward over the gathered lists on bf16 MFMA, variant that shares the coarse levels
+// (B = 16, d = 64 or 128, N a multiple of 256).
+//
+// The 16 fine query blocks under one level-1 query block use the same lists at every level >= 1 (Alg. 1,
+// enrichment loop: block i reads row i / B^l of I^(l)), i.e. the same coarse key/value tokens.  One
+// workgroup of 8 waves owns such a group; every wave owns two of its fine blocks.
+//   Phase A (levels >= 1): the workgroup stages each tile of two 16-token blocks (K and V rows) once in
+//     LDS, double-buffered; every wave reads the K operand once and multiplies it with both of its query
+//     blocks, likewise the transposed V operand, so the gather traffic of the coarse tokens is paid once
+//     per 256 queries instead of once per 16.
+//   Phase B (level 0): each wave walks the own K_0 blocks of each of its two query blocks, K rows straight
+//     from global memory into the A operand, V rows staged in a private LDS region.
+// Score tiles are computed transposed (S^T = K Q^T) so that the accumulator layout (4 keys x 1 query per
+// lane) is the B operand of O^T += V^T P^T; see mfma_common.h for the register layouts.
+#include <type_traits>
+
+#include "mfma_common.h"
+
+namespace llsa {
+
+typedef const __attribute__((address_space(1))) u32x4 *gvec_ptr;
+__device__ __forceinline__ u32x4 gload16(const char *base, unsigned off) {
+    return *reinterpret_cast<gvec_ptr>(reinterpret_cast<const __attribute__((address_space(1))) char *>(
+        reinterpret_cast<uintptr_t>(base)) + off);
+}
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
+    union { u32x4 u; bf16x8 b; } c;
+    c.u = v;
+    return c.b;
+}
+
+template <int D>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) attn_fwd_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q,
+                                                               uint16_t *__restrict__ O, float *__restrict__ LSE,
+                                                               int64_t N, int64_t total_wgs) {
+    constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, PARTS = D / 8, TILE = 32 * STRIDE;
+    constexpr int RND = (2 * 32 * PARTS) / 512;         // staging rounds of the workgroup per shared tile (K and V)
+    constexpr int VCH = D / 16, KPU = 64 / PARTS;       // private V staging of one wave (phase B)
+    __shared__ __attribute__((aligned(16))) char sh[2][2][TILE];      // [buffer][K | V]
+    __shared__ __attribute__((aligned(16))) char pw[8][TILE];         // per-wave V tile (phase B)
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int i16 = lane & 15, g = lane >> 4;
+    const int64_t groups = N >> 8;                                    // sibling groups per head
+    const int64_t wg = xcd_contiguous(blockIdx.x, total_wgs);
+    const int64_t bh = wg / groups, blk0 = (wg % groups) * 16;
+    const float sc2 = t.scale * kLog2e;
+
+    bf16x8 qop[2][KS];
+    f32x4 acc[2][NT];
+    float m[2], lsum[2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const uint16_t *qrow = Q + (bh * N + (blk0 + 2 * wave + b) * 16 + i16) * D + g * 8;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qop[b][s] = ld_bf16x8(qrow + 32 * s);
+#pragma unroll
+        for (int n = 0; n < NT; ++n) acc[b][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+        m[b] = -INFINITY;
+        lsum[b] = 0.f;
+    }
+
+    // softmax update of query block b for one tile (s0 / s1: S^T of the two halves) and O^T += V^T P^T
+    // with the V tile at `vt` (row-major, STRIDE bytes per key row)
+    auto softmax_pv = [&](auto bsel, f32x4 s0, f32x4 s1, int c0, int c1, float b0, float b1, const char *vt) {
+        constexpr int b = decltype(bsel)::value;
+        f32x4 s[2] = {s0, s1};
+        const float b2[2] = {b0, b1};
+        const int c[2] = {c0, c1};
+        float mx = -INFINITY;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s[h][r] = fmaf(s[h][r], sc2, b2[h]);
+                mx = fmaxf(mx, s[h][r]);
+            }
+        if (c[0] < 16 || c[1] < 16) {                                 // ragged or absent block: mask, redo the max
+            mx = -INFINITY;
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    if (4 * g + r >= c[h]) s[h][r] = -INFINITY;
+                    mx = fmaxf(mx, s[h][r]);
+                }
+        }
+        mx = rows_max(mx);
+        if (__builtin_amdgcn_ballot_w64(mx > m[b]) != 0) {            // some row's maximum rose: rescale
+            const float m_new = fmaxf(m[b], mx);
+            const float alpha = __builtin_amdgcn_exp2f(m[b] - m_new);
+            lsum[b] *= alpha;
+#pragma unroll
+            for (int n = 0; n < NT; ++n)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[b][n][r] *= alpha;
+            m[b] = m_new;
+        }
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                s[h][r] = __builtin_amdgcn_exp2f(s[h][r] - m[b]);
+                lsum[b] += s[h][r];
+            }
+        const bf16x8 pop = pack8(s[0], s[1]);
+        const char *base = vt + (4 * g + (i16 >> 2)) * STRIDE + (i16 & 3) * 8;
+#pragma unroll
+        for (int n = 0; n < NT; ++n)
+            acc[b][n] = mfma16(lds_tr_pair(base + n * 32, base + 16 * STRIDE + n * 32), pop, acc[b][n]);
+    };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
+
+    // ------------------------------------------------------------------ phase A: shared coarse levels
+    const int c_begin = t.nlev > 1 ? t.bseg[1] : t.bseg[t.nlev];     // first coarse block of the list
+    const int nbc = t.bseg[t.nlev] - c_begin;                         // coarse blocks
+    if (nbc > 0) {
+        BlockTable ctab;                                              // lane j: coarse block 64 * chunk + j
+        ctab.fill(t, bh, blk0, c_begin, 0, lane, D);
+        u32x4 sreg[RND];
+        auto load_shared = [&](int u) {                               // coarse blocks 2u, 2u + 1 -> registers
+            if (u > 0 && ((2 * u) & 63) == 0) ctab.fill(t, bh, blk0, c_begin, (2 * u) >> 6, lane, D);
+#pragma unroll
+            for (int r = 0; r < RND; ++r) {
+                const int cc = tid + 512 * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
+                const int key = c / PARTS, part = c % PARTS;
+                const int h = __builtin_amdgcn_readfirstlane(key >> 4);               // uniform within a wave
+                const int j = (2 * u + h < nbc) ? 2 * u + h : 2 * u;
+                const int cnt = (2 * u + h < nbc) ? ctab.count(j & 63) : 0;
+                const char *src = which ? ctab.V(j & 63) : ctab.K(j & 63);
+                const int row = min(key & 15, max(cnt, 1) - 1);
+                sreg[r] = gload16(src, (unsigned)((row * D + part * 8) * 2));
+            }
+        };
+        auto store_shared = [&](int buf) {
+#pragma unroll
+            for (int r = 0; r < RND; ++r) {
+                const int cc = tid + 512 * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
+                *reinterpret_cast<u32x4 *>(sh[buf][which] + (c / PARTS) * STRIDE + (c % PARTS) * 16) = sreg[r];
+            }
+        };
+        const int ntile = (nbc + 1) >> 1;
+        load_shared(0);
+        for (int u = 0; u < ntile; ++u) {
+            const int buf = u & 1;
+            store_shared(buf);
+            // per-half fields of this tile, before the table may be refilled for the next one
+            int cnt[2];
+            float bias2[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const bool have = 2 * u + h < nbc;
+                const int j = have ? 2 * u + h : 2 * u;
+                cnt[h] = have ? ctab.count(j & 63) : 0;
+                bias2[h] = ctab.bias(j & 63);
+            }
+            __syncthreads();                                          // tile u visible; buffer buf^1 free again
+            if (u + 1 < ntile) load_shared(u + 1);
+            const char *kt = sh[buf][0], *vt = sh[buf][1];
+            bf16x8 kop[2][KS];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    kop[h][ks] = *reinterpret_cast<const bf16x8 *>(kt + (h * 16 + i16) * STRIDE + g * 16 + ks * 64);
+            f32x4 s[2][2];
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    s[b][h] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) s[b][h] = mfma16(kop[h][ks], qop[b][ks], s[b][h]);
+                }
+            softmax_pv(B0{}, s[0][0], s[0][1], cnt[0], cnt[1], bias2[0], bias2[1], vt);
+            softmax_pv(B1{}, s[1][0], s[1][1], cnt[0], cnt[1], bias2[0], bias2[1], vt);
+        }
+    }
+
+    // ------------------------------------------------------------------ phase B: own level-0 blocks
+    const int nb0 = t.bseg[1];                                        // K_0 (the list always holds level 0)
+    char *my = pw[wave];
+    const unsigned koff = (unsigned)((i16 * D + g * 8) * 2);
+    unsigned voff[VCH];
+#pragma unroll
+    for (int u = 0; u < VCH; ++u) voff[u] = (unsigned)((((lane / PARTS + KPU * u) & 15) * D + (lane % PARTS) * 8) * 2);
+
+    auto phase_b = [&](auto bsel) {
+        constexpr int b = decltype(bsel)::value;
+        BlockTable tab;
+        tab.fill(t, bh, blk0 + 2 * wave + b, 0, 0, lane, D, 1);       // level 0 only (K_0 <= 64 blocks)
+        bf16x8 kop[2][KS];
+        u32x4 vreg[VCH];
+        auto load_tile = [&](int j0) {
+            const char *kp[2], *vp[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int j = (j0 + h < nb0) ? j0 + h : j0;           // an absent second half re-reads the first
+                kp[h] = tab.K(j);
+                vp[h] = tab.V(j);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) kop[h][s] = as_bf16x8(gload16(kp[h], koff + 64 * s));
+            }
+#pragma unroll
+            for (int u = 0; u < VCH; ++u) vreg[u] = gload16(vp[(KPU * u) >> 4], voff[u]);
+        };
+        load_tile(0);
+        for (int j0 = 0; j0 < nb0; j0 += 2) {
+            __builtin_amdgcn_wave_barrier();                          // one wave's LDS operations stay in order
+#pragma unroll
+            for (int u = 0; u < VCH; ++u)
+                *reinterpret_cast<u32x4 *>(my + (lane / PARTS + KPU * u) * STRIDE + (lane % PARTS) * 16) = vreg[u];
+            __builtin_amdgcn_wave_barrier();
+            f32x4 s[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) s[h] = mfma16(kop[h][ks], qop[b][ks], s[h]);
+            }
+            const int c1 = (j0 + 1 < nb0) ? 16 : 0;                   // level-0 blocks are always full
+            if (j0 + 2 < nb0) load_tile(j0 + 2);
+            softmax_pv(bsel, s[0], s[1], 16, c1, 0.f, 0.f, my);
+        }
+    };
+    phase_b(B0{});
+    phase_b(B1{});
+
+    // ------------------------------------------------------------------ epilogue
+#pragma unroll
+    for (int b = 0; b < 2; ++b) {
+        const float l = rows_sum(lsum[b]);
+        const float inv = 1.f / l;
+        const int64_t row = bh * N + (blk0 + 2 * wave + b) * 16 + i16;
+        uint16_t *orow = O + row * D + 4 * g;
+#pragma unroll
+        for (int n = 0; n < NT; ++n) {
+            u32x2 w;
+            w[0] = pack_bf16(acc[b][n][0] * inv, acc[b][n][1] * inv);
+            w[1] = pack_bf16(acc[b][n][2] * inv, acc[b][n][3] * inv);
+            *reinterpret_cast<u32x2 *>(orow + n * 16) = w;
+        }
+        if (g == 0) LSE[row] = (m[b] + __builtin_amdgcn_logf(l)) * kLn2;
+    }
+}
+
+hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
+                                  hipStream_t s) {
+    const int64_t wgs = (int64_t)p.bh * (p.N / 256);
+    dim3 grid((unsigned)wgs);
+    if (p.d != 64) return hipErrorInvalidValue;       // d = 128 would need more than 64 KB of LDS per workgroup
+    attn_fwd_shared_kernel<64><<<grid, 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N, wgs);
+    return hipGetLastError();
+}
+
+}  // namespace llsa

@@ -3,16 +3,20 @@
 // no floating-point atomics.
 // With P = exp(z - LSE), dP = dO V^T, dS = P o (dP - D):  dK = scale dS^T Q,  dV = P^T dO.
 //
-// One workgroup (4 waves) per (key block of 16 level-l tokens, split).  The queries that attend to the
-// block are the fine queries under the level-l query blocks listed for it, walked in groups of 16
-// consecutive queries; a tile is two groups.  The tiles of the workgroup's share are dealt round-robin
-// to its waves.  Per tile:
+// The queries that attend to a block of 16 level-l keys are the fine queries under the level-l query
+// blocks listed for it, walked in groups of 16 consecutive queries; a tile is two groups.  Per tile a wave
+// computes
 //   S = Q K^T, dP = dO V^T   (lane: 4 queries x 1 key)  ->  P, dS  ->
 //   dV^T += dO^T P,  dK^T += Q^T dS   (A = the Q / dO tile read transposed from LDS, B = P / dS).
-// The four waves' accumulators are summed through LDS in wave order, so the result does not depend on
-// timing.  Level 0 (no split) finishes in place: adds the parent token's share (adjoint of mean pooling)
-// and rounds once; coarser levels write fp32 partial sums, one slab per split, that a second kernel
-// adds up in split order.
+// Two kernels share that tile loop:
+//   dkv_coarse_kernel (levels >= 1): one workgroup of 4 waves per (key block, split); the tiles of its
+//     share are dealt round-robin to the waves, whose accumulators are summed through LDS in wave order;
+//     fp32 partial sums go to one slab per split and a second kernel adds the slabs in split order (and
+//     the share of the level above, the adjoint of mean pooling).
+//   dkv_fine_kernel (level 0): lists are short (K on average), so every wave takes one key block of its
+//     own; a key block whose list is long is instead worked on by all four waves together afterwards.
+//     The epilogue adds the parent token's share and rounds once to bf16.
+// Every sum has a fixed order, so results do not depend on timing.
 #include "mfma_common.h"
 
 namespace llsa {
@@ -26,93 +30,79 @@ struct DkvArgs {
     uint16_t *dK, *dV;                    // level-0 outputs
     int64_t N, n_l, rows, slab;           // rows = key blocks of this level per head that have lists
     int span_shift;                       // log2 of the 16-query groups per listed query block = 4 * level
-    int Kl_cnt, level, dense, splits;
+    int Kl_cnt, dense, splits;
     float sc2, bias2, scale;
 };
 
+template <int D> struct DkvShape {
+    static constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, VCH = D / 16, PARTS = D / 8, KPU = 64 / PARTS;
+    static constexpr int TILE = 32 * STRIDE;
+};
+
+// Tiles t_first, t_first + t_step, ... < t_end of one key block's query list, accumulated into accK / accV.
+// lst: the block's listed query-block rows (null when dense); groups: 16-query groups in the list.
 template <int D>
-__global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
-    constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, VCH = D / 16, PARTS = D / 8, KPU = 64 / PARTS;
-    constexpr int TILE = 32 * STRIDE;
-    __shared__ __attribute__((aligned(16))) char lds[4][2 * TILE];   // per wave: Q tile | dO tile
-
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+__device__ __forceinline__ void dkv_tile_loop(const DkvArgs &a, int64_t bh, const int32_t *lst, int64_t groups,
+                                              int64_t t_first, int64_t t_step, int64_t t_end,
+                                              const bf16x8 (&kop)[D / 32], const bf16x8 (&vop)[D / 32],
+                                              f32x4 (&accK)[D / 16], f32x4 (&accV)[D / 16], char *qt, char *gt,
+                                              int lane) {
+    using S = DkvShape<D>;
     const int i16 = lane & 15, g = lane >> 4;
-    const int64_t nkb = (a.n_l + 15) >> 4;                 // key blocks per head
-    const int64_t kbf = blockIdx.x / a.splits;             // flat key block
-    const int split = blockIdx.x % a.splits;
-    const int64_t bh = kbf / nkb, j = kbf % nkb;
-    const int cntk = (int)min((int64_t)16, a.n_l - j * 16);
-    char *qt = lds[wave], *gt = lds[wave] + TILE;
-
-    // this block's keys and values: B operands (columns = keys), held for the whole kernel
-    bf16x8 kop[KS], vop[KS];
-    {
-        const int64_t row = bh * a.n_l + j * 16 + min(i16, cntk - 1);
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            kop[s] = ld_bf16x8(a.Kl + row * D + g * 8 + 32 * s);
-            vop[s] = ld_bf16x8(a.Vl + row * D + g * 8 + 32 * s);
-        }
-    }
-    // the 16-query groups of this key block
-    const int32_t *lst = nullptr;
-    int64_t groups;
-    if (a.dense) {
-        groups = a.N >> 4;
-    } else {
-        const int32_t *Crow = a.C + bh * (a.rows + 1) + j;
-        const int32_t beg = Crow[0], end = Crow[1];
-        lst = a.Iq + bh * a.rows * a.Kl_cnt + beg;
-        groups = (int64_t)(end - beg) << a.span_shift;
-    }
-    const int64_t tiles = (groups + 1) >> 1;
-    const int64_t t_beg = tiles * split / a.splits, t_end = tiles * (split + 1) / a.splits;
     const int64_t span_mask = ((int64_t)1 << a.span_shift) - 1;
-
-    f32x4 accK[NT], accV[NT];
+    const int64_t entries = groups >> a.span_shift;
+    unsigned voff[S::VCH];
 #pragma unroll
-    for (int n = 0; n < NT; ++n) { accK[n] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[n] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    for (int u = 0; u < S::VCH; ++u) voff[u] = (unsigned)((((lane / S::PARTS + S::KPU * u) & 15) * D + (lane % S::PARTS) * 8) * 2);
 
-    int voff[VCH];
-#pragma unroll
-    for (int u = 0; u < VCH; ++u) voff[u] = (((lane / PARTS + KPU * u) & 15) * D + (lane % PARTS) * 8) * 2;
+    // the list entries, 64 at a time in one register (lane e: entry 64 * chunk + e)
+    int ecache = 0;
+    int64_t echunk = -1;
+    auto entry = [&](int64_t e) -> int64_t {
+        if ((e >> 6) != echunk) {
+            echunk = e >> 6;
+            const int64_t idx = echunk * 64 + lane;
+            ecache = idx < entries ? lst[idx] : 0;
+        }
+        return __builtin_amdgcn_readlane(ecache, (int)(e & 63));
+    };
 
-    u32x4 qreg[VCH], greg[VCH];
-    f32x4 lse[2], del[2];
-    int valid1;                                             // does the tile have its second group?
+    u32x4 qreg[S::VCH], greg[S::VCH];
+    float stat = 0.f;                                       // lane x: LSE (x < 32) or D (x >= 32) of tile query x % 32
+    int valid1 = 0;                                         // does the tile have its second group?
+    float *st = reinterpret_cast<float *>(gt + S::TILE);    // 64 floats behind the two tiles
     auto load_tile = [&](int64_t tile) {
         const char *qp[2], *gp[2];
         valid1 = 2 * tile + 1 < groups;
+        int64_t row0[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
             const int64_t gi = (h == 0 || valid1) ? 2 * tile + h : 2 * tile;   // an absent group re-reads the first
-            const int64_t q0 = a.dense ? gi * 16 : (((int64_t)lst[gi >> a.span_shift] << a.span_shift) + (gi & span_mask)) * 16;
-            const int64_t row0 = bh * a.N + q0;
-            lse[h] = *reinterpret_cast<const f32x4 *>(a.LSE + row0 + 4 * g);
-            del[h] = *reinterpret_cast<const f32x4 *>(a.Dsum + row0 + 4 * g);
-            qp[h] = reinterpret_cast<const char *>(a.Q + row0 * D);
-            gp[h] = reinterpret_cast<const char *>(a.dO + row0 * D);
+            const int64_t q0 = a.dense ? gi * 16 : ((entry(gi >> a.span_shift) << a.span_shift) + (gi & span_mask)) * 16;
+            row0[h] = bh * a.N + q0;
+            qp[h] = reinterpret_cast<const char *>(a.Q + row0[h] * D);
+            gp[h] = reinterpret_cast<const char *>(a.dO + row0[h] * D);
         }
+        stat = ((lane & 32) ? a.Dsum : a.LSE)[((lane & 16) ? row0[1] : row0[0]) + i16];
 #pragma unroll
-        for (int u = 0; u < VCH; ++u) {
-            const int h = (KPU * u) >> 4;
+        for (int u = 0; u < S::VCH; ++u) {
+            const int h = (S::KPU * u) >> 4;
             qreg[u] = *reinterpret_cast<const u32x4 *>(qp[h] + voff[u]);
             greg[u] = *reinterpret_cast<const u32x4 *>(gp[h] + voff[u]);
         }
     };
 
-    int64_t tile = t_beg + wave;
+    int64_t tile = t_first;
     if (tile < t_end) load_tile(tile);
     while (tile < t_end) {
-        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_wave_barrier();                    // one wave's LDS operations stay in order
 #pragma unroll
-        for (int u = 0; u < VCH; ++u) {
-            const int q = lane / PARTS + KPU * u, part = lane % PARTS;
-            *reinterpret_cast<u32x4 *>(qt + q * STRIDE + part * 16) = qreg[u];
-            *reinterpret_cast<u32x4 *>(gt + q * STRIDE + part * 16) = greg[u];
+        for (int u = 0; u < S::VCH; ++u) {
+            const int q = lane / S::PARTS + S::KPU * u, part = lane % S::PARTS;
+            *reinterpret_cast<u32x4 *>(qt + q * S::STRIDE + part * 16) = qreg[u];
+            *reinterpret_cast<u32x4 *>(gt + q * S::STRIDE + part * 16) = greg[u];
         }
+        st[lane] = stat;
         __builtin_amdgcn_wave_barrier();
 
         f32x4 s[2], dp[2];
@@ -120,16 +110,19 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
         for (int h = 0; h < 2; ++h) {
             s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
             dp[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-            const char *qrow = qt + (h * 16 + i16) * STRIDE + g * 16, *grow = gt + (h * 16 + i16) * STRIDE + g * 16;
+            const char *qrow = qt + (h * 16 + i16) * S::STRIDE + g * 16, *grow = gt + (h * 16 + i16) * S::STRIDE + g * 16;
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+            for (int ks = 0; ks < S::KS; ++ks) {
                 s[h] = mfma16(*reinterpret_cast<const bf16x8 *>(qrow + ks * 64), kop[ks], s[h]);
                 dp[h] = mfma16(*reinterpret_cast<const bf16x8 *>(grow + ks * 64), vop[ks], dp[h]);
             }
         }
-        const f32x4 l2[2] = {lse[0], lse[1]}, dl[2] = {del[0], del[1]};
+        // this lane's 4 queries per half: rows 4g .. 4g+3
+        const f32x4 l2[2] = {*reinterpret_cast<const f32x4 *>(st + 4 * g), *reinterpret_cast<const f32x4 *>(st + 16 + 4 * g)};
+        const f32x4 dl[2] = {*reinterpret_cast<const f32x4 *>(st + 32 + 4 * g),
+                             *reinterpret_cast<const f32x4 *>(st + 48 + 4 * g)};
         const int v1 = valid1;
-        const int64_t next = tile + 4;
+        const int64_t next = tile + t_step;
         if (next < t_end) load_tile(next);
 
 #pragma unroll
@@ -145,27 +138,29 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
             dp[1] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
         const bf16x8 pop = pack8(s[0], s[1]), dsop = pack8(dp[0], dp[1]);
-        const int boff = (4 * g + (i16 >> 2)) * STRIDE + (i16 & 3) * 8;
+        const int boff = (4 * g + (i16 >> 2)) * S::STRIDE + (i16 & 3) * 8;
 #pragma unroll
-        for (int n = 0; n < NT; ++n) {
-            accV[n] = mfma16(lds_tr_pair(gt + boff + n * 32, gt + boff + 16 * STRIDE + n * 32), pop, accV[n]);
-            accK[n] = mfma16(lds_tr_pair(qt + boff + n * 32, qt + boff + 16 * STRIDE + n * 32), dsop, accK[n]);
+        for (int n = 0; n < S::NT; ++n) {
+            accV[n] = mfma16(lds_tr_pair(gt + boff + n * 32, gt + boff + 16 * S::STRIDE + n * 32), pop, accV[n]);
+            accK[n] = mfma16(lds_tr_pair(qt + boff + n * 32, qt + boff + 16 * S::STRIDE + n * 32), dsop, accK[n]);
         }
         tile = next;
     }
+}
 
-    // sum the four waves' accumulators in wave order through LDS (reusing the tile buffers)
-    __syncthreads();
-    float *red = reinterpret_cast<float *>(&lds[0][0]);     // [wave][2 * NT][64 lanes] float4 slots
-    constexpr int SLOTS = 2 * NT;
-    static_assert(4 * SLOTS * 64 * 16 <= 4 * 2 * TILE, "reduction buffer must fit in the tile buffers");
+// Sum of the four waves' accumulators in wave order through LDS; wave w ends up owning slots w, w + 4, ...
+// (slot = which * NT + n, which: 0 = dK, 1 = dV) and hands each finished slot to `emit(slot, sum)`.
+template <int D, class Emit>
+__device__ __forceinline__ void dkv_reduce_waves(float *red, int wave, int lane, const f32x4 (&accK)[D / 16],
+                                                 const f32x4 (&accV)[D / 16], Emit emit) {
+    constexpr int NT = D / 16, SLOTS = 2 * NT;
+    __syncthreads();                                        // everyone is done with the tile buffers
 #pragma unroll
     for (int n = 0; n < NT; ++n) {
         *reinterpret_cast<f32x4 *>(red + ((wave * SLOTS + n) * 64 + lane) * 4) = accK[n];
         *reinterpret_cast<f32x4 *>(red + ((wave * SLOTS + NT + n) * 64 + lane) * 4) = accV[n];
     }
     __syncthreads();
-    // wave w finishes slots w, w+4, ...: slot = which * NT + n
     for (int slot = wave; slot < SLOTS; slot += 4) {
         f32x4 sum = *reinterpret_cast<const f32x4 *>(red + ((0 * SLOTS + slot) * 64 + lane) * 4);
 #pragma unroll
@@ -174,29 +169,142 @@ __global__ void __launch_bounds__(256) dkv_mfma_kernel(DkvArgs a) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) sum[r] += x[r];
         }
-        const bool isV = slot >= NT;
-        const int n = isV ? slot - NT : slot;
-        if (i16 >= cntk) continue;                          // rows past the end of a ragged coarsest level
-        const int64_t tok = bh * a.n_l + j * 16 + i16;
+        emit(slot, sum);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void dkv_load_keys(const DkvArgs &a, int64_t row, int lane, bf16x8 (&kop)[D / 32],
+                                              bf16x8 (&vop)[D / 32]) {
+    const int g = lane >> 4;
+#pragma unroll
+    for (int s = 0; s < D / 32; ++s) {
+        kop[s] = ld_bf16x8(a.Kl + row * D + g * 8 + 32 * s);
+        vop[s] = ld_bf16x8(a.Vl + row * D + g * 8 + 32 * s);
+    }
+}
+
+// ----------------------------------------------------------------------------------------- levels >= 1
+template <int D>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2))) dkv_coarse_kernel(DkvArgs a) {
+    using S = DkvShape<D>;
+    __shared__ __attribute__((aligned(16))) char lds[4][2 * S::TILE + 256];   // per wave: Q tile | dO tile | LSE, D
+    static_assert(4 * 2 * S::NT * 64 * 16 <= 4 * 2 * S::TILE, "reduction buffer must fit in the tile buffers");
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i16 = lane & 15, g = lane >> 4;
+    const int64_t nkb = (a.n_l + 15) >> 4;                 // key blocks per head
+    const int64_t kbf = blockIdx.x / a.splits;             // flat key block
+    const int split = blockIdx.x % a.splits;
+    const int64_t bh = kbf / nkb, j = kbf % nkb;
+    const int cntk = (int)min((int64_t)16, a.n_l - j * 16);
+
+    bf16x8 kop[S::KS], vop[S::KS];                          // B operands (columns = keys), held throughout
+    dkv_load_keys<D>(a, bh * a.n_l + j * 16 + min(i16, cntk - 1), lane, kop, vop);
+    const int32_t *lst = nullptr;
+    int64_t groups;
+    if (a.dense) {
+        groups = a.N >> 4;
+    } else {
+        const int32_t *Crow = a.C + bh * (a.rows + 1) + j;
+        const int32_t beg = Crow[0], end = Crow[1];
+        lst = a.Iq + bh * a.rows * a.Kl_cnt + beg;
+        groups = (int64_t)(end - beg) << a.span_shift;
+    }
+    const int64_t tiles = (groups + 1) >> 1;
+    const int64_t t_beg = tiles * split / a.splits, t_end = tiles * (split + 1) / a.splits;
+
+    f32x4 accK[S::NT], accV[S::NT];
+#pragma unroll
+    for (int n = 0; n < S::NT; ++n) { accK[n] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[n] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+    dkv_tile_loop<D>(a, bh, lst, groups, t_beg + wave, 4, t_end, kop, vop, accK, accV, lds[wave], lds[wave] + S::TILE, lane);
+
+    dkv_reduce_waves<D>(reinterpret_cast<float *>(&lds[0][0]), wave, lane, accK, accV, [&](int slot, f32x4 sum) {
+        const bool isV = slot >= S::NT;
+        const int n = isV ? slot - S::NT : slot;
+        if (i16 >= cntk) return;                            // rows past the end of a ragged coarsest level
+        if (!isV)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sum[r] *= a.scale;
+        float *dst = (isV ? a.partV : a.partK) + (int64_t)split * a.slab;
+        *reinterpret_cast<f32x4 *>(dst + (bh * a.n_l + j * 16 + i16) * D + n * 16 + 4 * g) = sum;
+    });
+}
+
+// ---------------------------------------------------------------------------------------------- level 0
+constexpr int kSoloMax = 24;                                // longest list (entries) one wave takes alone
+
+template <int D>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 1))) dkv_fine_kernel(DkvArgs a) {
+    using S = DkvShape<D>;
+    __shared__ __attribute__((aligned(16))) char lds[4][2 * S::TILE + 256];
+    __shared__ int len_sh[4];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int i16 = lane & 15, g = lane >> 4;
+    const int64_t nkb = a.n_l >> 4;                        // key blocks per head (a multiple of 4)
+    const int64_t kb0 = (int64_t)blockIdx.x * 4;           // this workgroup's four key blocks (same head)
+    const int64_t bh = kb0 / nkb;
+
+    // level-0 epilogue: scale dK, add the parent token's share (adjoint of mean pooling), round once
+    auto emit = [&](int64_t j, int slot, f32x4 sum) {
+        const bool isV = slot >= S::NT;
+        const int n = isV ? slot - S::NT : slot;
         const int col = n * 16 + 4 * g;                     // lane holds 4 consecutive channels of key i16
         if (!isV)
 #pragma unroll
             for (int r = 0; r < 4; ++r) sum[r] *= a.scale;
-        if (a.level > 0) {
-            float *dst = (isV ? a.partV : a.partK) + (int64_t)split * a.slab;
-            *reinterpret_cast<f32x4 *>(dst + tok * D + col) = sum;
-        } else {
-            const float *par = isV ? a.parV : a.parK;
-            if (par) {
-                const f32x4 pv = *reinterpret_cast<const f32x4 *>(par + (bh * (a.n_l >> 4) + j) * D + col);
+        const float *par = isV ? a.parV : a.parK;
+        if (par) {
+            const f32x4 pv = *reinterpret_cast<const f32x4 *>(par + (bh * nkb + j) * D + col);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) sum[r] += pv[r] * 0.0625f;
-            }
-            u32x2 w;
-            w[0] = pack_bf16(sum[0], sum[1]);
-            w[1] = pack_bf16(sum[2], sum[3]);
-            *reinterpret_cast<u32x2 *>((isV ? a.dV : a.dK) + tok * D + col) = w;
+            for (int r = 0; r < 4; ++r) sum[r] += pv[r] * 0.0625f;
         }
+        u32x2 w;
+        w[0] = pack_bf16(sum[0], sum[1]);
+        w[1] = pack_bf16(sum[2], sum[3]);
+        *reinterpret_cast<u32x2 *>((isV ? a.dV : a.dK) + (bh * a.n_l + j * 16 + i16) * D + col) = w;
+    };
+
+    // ---- each wave alone on its own key block, if that block's list is short
+    {
+        const int64_t j = kb0 % nkb + wave;
+        const int32_t *Crow = a.C + bh * (a.rows + 1) + j;
+        const int32_t beg = Crow[0], len = Crow[1] - beg;
+        if (lane == 0) len_sh[wave] = len;
+        if (len <= kSoloMax) {
+            bf16x8 kop[S::KS], vop[S::KS];
+            f32x4 accK[S::NT], accV[S::NT];
+#pragma unroll
+            for (int n = 0; n < S::NT; ++n) { accK[n] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[n] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+            if (len > 0) {
+                dkv_load_keys<D>(a, bh * a.n_l + j * 16 + i16, lane, kop, vop);
+                dkv_tile_loop<D>(a, bh, a.Iq + bh * a.rows * a.Kl_cnt + beg, len, 0, 1, ((int64_t)len + 1) >> 1, kop, vop,
+                                 accK, accV, lds[wave], lds[wave] + S::TILE, lane);
+            }
+#pragma unroll
+            for (int n = 0; n < S::NT; ++n) { emit(j, n, accK[n]); emit(j, S::NT + n, accV[n]); }
+        }
+    }
+    __syncthreads();
+    // ---- long lists: all four waves together, one key block after the other
+    for (int w = 0; w < 4; ++w) {
+        const int len = len_sh[w];
+        if (len <= kSoloMax) continue;                      // uniform over the workgroup
+        const int64_t j = kb0 % nkb + w;
+        const int32_t beg = a.C[bh * (a.rows + 1) + j];
+        bf16x8 kop[S::KS], vop[S::KS];
+        f32x4 accK[S::NT], accV[S::NT];
+#pragma unroll
+        for (int n = 0; n < S::NT; ++n) { accK[n] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[n] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        dkv_load_keys<D>(a, bh * a.n_l + j * 16 + i16, lane, kop, vop);
+        dkv_tile_loop<D>(a, bh, a.Iq + bh * a.rows * a.Kl_cnt + beg, len, wave, 4, ((int64_t)len + 1) >> 1, kop, vop, accK,
+                         accV, lds[wave], lds[wave] + S::TILE, lane);
+        dkv_reduce_waves<D>(reinterpret_cast<float *>(&lds[0][0]), wave, lane, accK, accV,
+                            [&](int slot, f32x4 sum) { emit(j, slot, sum); });
+        __syncthreads();                                    // the reduction buffer is the next round's tile space
     }
 }
 
@@ -258,13 +366,18 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
     a.rows = a.dense ? 0 : p.n[l + 1];
     a.span_shift = a.dense ? 0 : 4 * l;
     a.Kl_cnt = a.dense ? 0 : p.Kl[l];
-    a.level = l;
     a.sc2 = p.scale * kLog2e; a.bias2 = t.bias[l] * kLog2e; a.scale = p.scale;
+    if (l == 0) {                                           // N % 64 == 0: four key blocks per workgroup, one head
+        dim3 grid((unsigned)(key_blocks / 4));
+        if (p.d == 64) dkv_fine_kernel<64><<<grid, 256, 0, s>>>(a);
+        else dkv_fine_kernel<128><<<grid, 256, 0, s>>>(a);
+        return hipGetLastError();
+    }
     dim3 grid((unsigned)(key_blocks * a.splits));
-    if (p.d == 64) dkv_mfma_kernel<64><<<grid, 256, 0, s>>>(a);
-    else dkv_mfma_kernel<128><<<grid, 256, 0, s>>>(a);
+    if (p.d == 64) dkv_coarse_kernel<64><<<grid, 256, 0, s>>>(a);
+    else dkv_coarse_kernel<128><<<grid, 256, 0, s>>>(a);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || l == 0) return e;
+    if (e != hipSuccess) return e;
     // fold the slabs (and the level above) into this level's fp32 gradient
     const int64_t total4 = (int64_t)p.bh * p.n[l] * p.d / 4;
     const bool has_up = l < p.Le;

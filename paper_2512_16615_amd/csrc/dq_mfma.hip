@@ -15,7 +15,7 @@ __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w 
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
 template <int D>
-__global__ void __launch_bounds__(256) dq_mfma_kernel(LevelTable t, const uint16_t *__restrict__ Q,
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2))) dq_mfma_kernel(LevelTable t, const uint16_t *__restrict__ Q,
                                                        const uint16_t *__restrict__ O, const uint16_t *__restrict__ dO,
                                                        const float *__restrict__ LSE, float *__restrict__ Dsum,
                                                        uint16_t *__restrict__ dQ, int64_t N, int64_t total_wgs) {
@@ -57,7 +57,7 @@ __global__ void __launch_bounds__(256) dq_mfma_kernel(LevelTable t, const uint16
     const int nb = t.bseg[t.nlev];
 
     BlockTable tab;
-    tab.fill(t, bh, blk, 0, lane, D);
+    tab.fill(t, bh, blk, 0, 0, lane, D);
     const int koff = (i16 * D + g * 8) * 2;
     int voff[VCH];
 #pragma unroll
@@ -69,7 +69,7 @@ __global__ void __launch_bounds__(256) dq_mfma_kernel(LevelTable t, const uint16
     int cnt[2];
 
     auto load_tile = [&](int j0) {
-        if (j0 > 0 && (j0 & 63) == 0) tab.fill(t, bh, blk, j0 >> 6, lane, D);
+        if (j0 > 0 && (j0 & 63) == 0) tab.fill(t, bh, blk, 0, j0 >> 6, lane, D);
         const char *kp[2], *vp[2];
 #pragma unroll
         for (int h = 0; h < 2; ++h) {

@@ -67,6 +67,9 @@ hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
 
 // ---- bf16 MFMA kernels (B = 16, d = 64 or 128) ----
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);
+// variant that shares the coarse levels among the 16 sibling query blocks of a workgroup (d = 64, N % 256 == 0)
+hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
+                                  hipStream_t s);
 // also writes D = rowsum(dO * O) for the key-major kernels that follow
 hipError_t launch_dq_mfma(const Plan &p, const LevelTable &t, const void *Q, const void *O, const void *dO,
                           const float *LSE, float *D, void *dQ, hipStream_t s);

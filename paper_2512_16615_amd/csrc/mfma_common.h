@@ -95,12 +95,15 @@ struct BlockTable {
     float bias2;             // log2 of the level's token weight
     int cnt;                 // valid rows: 16, fewer in the last block of a ragged coarsest level, 0 past the end
 
-    __device__ __forceinline__ void fill(const LevelTable &t, int64_t bh, int64_t blk, int chunk, int lane, int d) {
-        const int jb = chunk * 64 + lane;
+    // lane j describes list block base + 64 * chunk + j; only levels below lev_end are looked at
+    __device__ __forceinline__ void fill(const LevelTable &t, int64_t bh, int64_t blk, int base, int chunk, int lane,
+                                         int d, int lev_end = kMaxL + 1) {
+        const int jb = base + chunk * 64 + lane;
         kptr = vptr = 0;
         bias2 = 0.f;
         cnt = 0;
-        for (int l = 0; l < t.nlev; ++l) {                       // wave-uniform loop over the levels in the list
+        const int nl = min(t.nlev, lev_end);
+        for (int l = 0; l < nl; ++l) {                           // wave-uniform loop over the levels in the list
             const int b0 = pick(t.bseg, l), b1 = pick(t.bseg, l + 1);
             const int64_t n_l = pick(t.n, l);
             const char *Kb = static_cast<const char *>(pick(t.K, l)), *Vb = static_cast<const char *>(pick(t.V, l));
