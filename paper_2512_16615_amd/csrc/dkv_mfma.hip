@@ -195,8 +195,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
     const int64_t nkb = (a.n_l + 15) >> 4;                 // key blocks per head
-    const int64_t kbf = blockIdx.x / a.splits;             // flat key block
-    const int split = blockIdx.x % a.splits;
+    const int64_t wgid = xcd_contiguous(blockIdx.x, gridDim.x);   // neighbouring key blocks share query tiles in L2
+    const int64_t kbf = wgid / a.splits;                   // flat key block
+    const int split = (int)(wgid % a.splits);
     const int64_t bh = kbf / nkb, j = kbf % nkb;
     const int cntk = (int)min((int64_t)16, a.n_l - j * 16);
 
@@ -245,6 +246,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
     const int64_t nkb = a.n_l >> 4;                        // key blocks per head (a multiple of 4)
+    // plain order: hot key blocks cluster, and round-robin dispatch spreads a cluster over the XCDs
     const int64_t kb0 = (int64_t)blockIdx.x * 4;           // this workgroup's four key blocks (same head)
     const int64_t bh = kb0 / nkb;
 

@@ -196,6 +196,7 @@ __global__ void select_kernel(const T *Ql, const T *Kl, int64_t n_l, int d, int 
 }
 
 hipError_t launch_select(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s) {
+    if (p.desc.kernel_path == 0 && select_fast_ok(p, l)) return launch_select_fast(p, l, ws, parent, out, s);
     const char *w = static_cast<const char *>(ws);
     const bool top = (l == p.L);
     const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
@@ -317,23 +318,34 @@ hipError_t launch_bwd_pre(const Plan &p, const void *O, const void *dO, float *D
 // count -> exclusive scan -> fill -> per-key ascending order.  Counting and filling use integer atomics;
 // the order they leave inside a key's list depends on timing, so a last pass sorts every list, which makes
 // the result (and with it the summation order of dK / dV) the same on every run.
-__global__ void csc_zero_kernel(int32_t *cnt, int64_t n) {
+// All levels run in the same launches: blockIdx.y selects the level.
+struct CscLevel {
+    const int32_t *I;            // I^(l) [bh, T, Kl]
+    int32_t *cnt, *C, *Iq, *Iq_tmp;
+    int64_t T, eph, total, nk;   // keys per head, entries per head, entries, keys
+    int Kl;
+};
+struct CscLevels { CscLevel lv[kMaxL]; };
+
+__global__ void csc_zero_kernel(CscLevels a) {
+    const CscLevel &L = a.lv[blockIdx.y];
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n) cnt[i] = 0;
+    if (i < L.nk) L.cnt[i] = 0;
 }
-__global__ void csc_count_kernel(const int32_t *I, int32_t *cnt, int64_t entries_per_head, int64_t T,
-                                 int64_t total) {
+__global__ void csc_count_kernel(CscLevels a) {
+    const CscLevel &L = a.lv[blockIdx.y];
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
-    const int64_t bh = e / entries_per_head;
-    atomicAdd(&cnt[bh * T + I[e]], 1);
+    if (e >= L.total) return;
+    const int64_t bh = e / L.eph;
+    atomicAdd(&L.cnt[bh * L.T + L.I[e]], 1);
 }
-// one workgroup per head: C = exclusive scan of cnt (T+1 entries), cnt reset to 0 for the fill pass
-__global__ void __launch_bounds__(1024) csc_scan_kernel(int32_t *cnt, int32_t *C, int64_t T) {
+// one workgroup per (head, level): C = exclusive scan of cnt (T+1 entries), cnt reset to 0 for the fill pass
+__global__ void __launch_bounds__(1024) csc_scan_kernel(CscLevels a) {
     __shared__ int32_t wsum[16];
     __shared__ int32_t carry;
-    const int64_t bh = blockIdx.x;
-    int32_t *cn = cnt + bh * T, *Co = C + bh * (T + 1);
+    const CscLevel &L = a.lv[blockIdx.y];
+    const int64_t bh = blockIdx.x, T = L.T;
+    int32_t *cn = L.cnt + bh * T, *Co = L.C + bh * (T + 1);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry = 0;
     __syncthreads();
@@ -357,46 +369,68 @@ __global__ void __launch_bounds__(1024) csc_scan_kernel(int32_t *cnt, int32_t *C
     }
     if (threadIdx.x == 0) Co[T] = carry;
 }
-__global__ void csc_fill_kernel(const int32_t *I, const int32_t *C, int32_t *cur, int32_t *Iq_tmp,
-                                int64_t entries_per_head, int Kl, int64_t T, int64_t total) {
+__global__ void csc_fill_kernel(CscLevels a) {
+    const CscLevel &L = a.lv[blockIdx.y];
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
-    const int64_t bh = e / entries_per_head, within = e % entries_per_head;
-    const int32_t key = I[e];
-    const int32_t slot = C[bh * (T + 1) + key] + atomicAdd(&cur[bh * T + key], 1);
-    Iq_tmp[bh * entries_per_head + slot] = (int32_t)(within / Kl);
+    if (e >= L.total) return;
+    const int64_t bh = e / L.eph, within = e % L.eph;
+    const int32_t key = L.I[e];
+    const int32_t slot = L.C[bh * (L.T + 1) + key] + atomicAdd(&L.cnt[bh * L.T + key], 1);
+    L.Iq_tmp[bh * L.eph + slot] = (int32_t)(within / L.Kl);
 }
-// one wave per key: rank-sort its list (entries are distinct query rows)
-__global__ void __launch_bounds__(256) csc_sort_kernel(const int32_t *C, const int32_t *Iq_tmp, int32_t *Iq,
-                                                       int64_t entries_per_head, int64_t T, int64_t total_keys) {
+// one wave per key: rank-sort its list (entries are distinct query rows).  Lists of up to 64 entries are
+// ranked in registers; longer ones fall back to re-reading the list.
+__global__ void __launch_bounds__(256) csc_sort_kernel(CscLevels a) {
+    const CscLevel &L = a.lv[blockIdx.y];
     const int lane = threadIdx.x & 63;
     const int64_t key_flat = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (key_flat >= total_keys) return;
-    const int64_t bh = key_flat / T, key = key_flat % T;
-    const int32_t beg = C[bh * (T + 1) + key], end = C[bh * (T + 1) + key + 1];
-    const int32_t *src = Iq_tmp + bh * entries_per_head;
-    int32_t *dst = Iq + bh * entries_per_head;
-    for (int32_t a = beg + lane; a < end; a += 64) {
-        const int32_t x = src[a];
+    if (key_flat >= L.nk) return;
+    const int64_t bh = key_flat / L.T, key = key_flat % L.T;
+    const int32_t beg = L.C[bh * (L.T + 1) + key], end = L.C[bh * (L.T + 1) + key + 1];
+    const int32_t *src = L.Iq_tmp + bh * L.eph;
+    int32_t *dst = L.Iq + bh * L.eph;
+    const int32_t n = end - beg;
+    if (n <= 64) {
+        const int32_t x = lane < n ? src[beg + lane] : 0x7fffffff;
+        int32_t rank = 0;
+        for (int b = 0; b < n; ++b) rank += (__builtin_amdgcn_readlane(x, b) < x) ? 1 : 0;
+        if (lane < n) dst[beg + rank] = x;
+        return;
+    }
+    for (int32_t i = beg + lane; i < end; i += 64) {
+        const int32_t x = src[i];
         int32_t rank = 0;
         for (int32_t b = beg; b < end; ++b) rank += (src[b] < x) ? 1 : 0;
         dst[beg + rank] = x;
     }
 }
 
-hipError_t launch_csc(const Plan &p, int l, const int32_t *indices, void *ws, hipStream_t s) {
+// Alg. 2 for levels 0 .. top (the levels whose lists the backward uses), five launches in all
+hipError_t launch_csc(const Plan &p, int top, const int32_t *indices, void *ws, hipStream_t s) {
     char *w = static_cast<char *>(ws);
-    const int64_t T = p.n[l + 1];
-    const int64_t eph = T * p.Kl[l], total = eph * p.bh;
-    const int32_t *I = reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(indices) + p.idx_off[l]);
-    int32_t *cnt = (int32_t *)(w + p.cnt_off[l]), *C = (int32_t *)(w + p.C_off[l]);
-    int32_t *Iq = (int32_t *)(w + p.Iq_off[l]), *Iqt = (int32_t *)(w + p.Iqtmp_off[l]);
-    const int64_t nk = T * p.bh;
-    csc_zero_kernel<<<(unsigned)((nk + 255) / 256), 256, 0, s>>>(cnt, nk);
-    csc_count_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(I, cnt, eph, T, total);
-    csc_scan_kernel<<<p.bh, 1024, 0, s>>>(cnt, C, T);
-    csc_fill_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>(I, C, cnt, Iqt, eph, p.Kl[l], T, total);
-    csc_sort_kernel<<<(unsigned)((nk + 3) / 4), 256, 0, s>>>(C, Iqt, Iq, eph, T, nk);
+    CscLevels a;
+    int64_t max_nk = 0, max_total = 0;
+    for (int l = 0; l <= top; ++l) {
+        CscLevel &L = a.lv[l];
+        L.T = p.n[l + 1];
+        L.Kl = p.Kl[l];
+        L.eph = L.T * L.Kl;
+        L.total = L.eph * p.bh;
+        L.nk = L.T * p.bh;
+        L.I = reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(indices) + p.idx_off[l]);
+        L.cnt = (int32_t *)(w + p.cnt_off[l]);
+        L.C = (int32_t *)(w + p.C_off[l]);
+        L.Iq = (int32_t *)(w + p.Iq_off[l]);
+        L.Iq_tmp = (int32_t *)(w + p.Iqtmp_off[l]);
+        if (L.nk > max_nk) max_nk = L.nk;
+        if (L.total > max_total) max_total = L.total;
+    }
+    const unsigned nl = (unsigned)(top + 1);
+    csc_zero_kernel<<<dim3((unsigned)((max_nk + 255) / 256), nl), 256, 0, s>>>(a);
+    csc_count_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
+    csc_scan_kernel<<<dim3(p.bh, nl), 1024, 0, s>>>(a);
+    csc_fill_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
+    csc_sort_kernel<<<dim3((unsigned)((max_nk + 3) / 4), nl), 256, 0, s>>>(a);
     return hipGetLastError();
 }
 

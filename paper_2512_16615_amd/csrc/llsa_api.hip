@@ -261,7 +261,7 @@ llsa_status llsa_forward(const llsa_plan_t *plan, const void *Q, const void *K, 
 llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices, void *workspace, void *hip_stream) {
     if (!plan || !indices || !workspace) return LLSA_ERR_NULL;
     const Plan &p = plan->p;
-    for (int l = 0; l < p.L; ++l) LLSA_TRY(launch_csc(p, l, indices, workspace, (hipStream_t)hip_stream));
+    LLSA_TRY(launch_csc(p, p.L - 1, indices, workspace, (hipStream_t)hip_stream));
     return LLSA_OK;
 }
 
@@ -286,7 +286,7 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     {
         StageScope sc(kTranspose, call, s);
         const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
-        for (int l = 0; l <= top_listed; ++l) LLSA_TRY(launch_csc(p, l, indices, workspace, s));
+        LLSA_TRY(launch_csc(p, top_listed, indices, workspace, s));
     }
     LevelTable t = make_level_table(p, K, V, indices, workspace);
     {

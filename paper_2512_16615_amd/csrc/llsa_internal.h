@@ -58,12 +58,16 @@ hipError_t launch_select(const Plan &p, int l, const void *ws, const int32_t *pa
 hipError_t launch_attn_fwd_generic(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                    hipStream_t s);
 hipError_t launch_bwd_pre(const Plan &p, const void *O, const void *dO, float *D, hipStream_t s);
-hipError_t launch_csc(const Plan &p, int l, const int32_t *I, void *ws, hipStream_t s);
+hipError_t launch_csc(const Plan &p, int top_level, const int32_t *I, void *ws, hipStream_t s);  // levels 0..top_level
 hipError_t launch_dq_generic(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
                              const float *D, void *dQ, hipStream_t s);
 hipError_t launch_dkv_generic(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO,
                               const float *LSE, const float *D, void *ws, void *dK, void *dV, hipStream_t s);
 hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
+
+// ---- fast selection (bf16, B = 16, <= 128 candidates, K <= 16) ----
+bool select_fast_ok(const Plan &p, int l);
+hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s);
 
 // ---- bf16 MFMA kernels (B = 16, d = 64 or 128) ----
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);
@@ -73,6 +77,8 @@ hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void
 // also writes D = rowsum(dO * O) for the key-major kernels that follow
 hipError_t launch_dq_mfma(const Plan &p, const LevelTable &t, const void *Q, const void *O, const void *dO,
                           const float *LSE, float *D, void *dQ, hipStream_t s);
+hipError_t launch_dq_shared(const Plan &p, const LevelTable &t, const void *Q, const void *O, const void *dO,
+                            const float *LSE, float *D, void *dQ, hipStream_t s);
 // key-major dK/dV of level l; levels >= 1 also fold their split slabs and the level above into the
 // level's fp32 gradient buffer, so they must be launched from the coarsest level down
 hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO, const float *LSE,

@@ -1,0 +1,122 @@
+// Hierarchical Top-K selection, one level (Alg. 1, selection loop), fast path for bf16, B = 16, at most
+// 128 candidates per query block and K <= 16.
+//
+// One workgroup (256 threads) per level-l query block of 16 query tokens.  The candidate key rows (all
+// n_L tokens at the coarsest level, the 16 * K_l children of the parent's picks below it) and the 16
+// query rows are staged once in LDS; lane (row r, column group c) scores candidates c, c + 16, ... of
+// row r, so the 128 scores of a row sit in one 16-lane row group and the Top-K runs in registers.
+// Scores are fp32 fused-multiply-add chains over channels 0 .. d-1 in order (the same chain on every
+// launch shape), ties go to the lower key id, rows are written in ascending id order.
+#include "mfma_common.h"
+
+namespace llsa {
+
+__device__ __forceinline__ void unpack8(u32x4 w, float *f) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[2 * i] = __uint_as_float(w[i] << 16);
+        f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+
+template <int D>
+__global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
+                                                           int64_t n_l, const int32_t *__restrict__ parent, int Kp,
+                                                           int Kout, int32_t *__restrict__ out, int C, int64_t nblk) {
+    constexpr int STRIDE = 2 * D + 16;                      // bytes per staged row: keeps 16-byte reads conflict-free
+    constexpr int CH = D / 8;                               // 16-byte chunks per row
+    __shared__ __attribute__((aligned(16))) char kc[128 * STRIDE];
+    __shared__ __attribute__((aligned(16))) char qs[16 * STRIDE];
+
+    const int tid = threadIdx.x;
+    const int64_t bh = blockIdx.x / nblk, r = blockIdx.x % nblk;
+    const uint16_t *Kb = Kl + bh * n_l * D;
+    const int32_t *prow = parent ? parent + (bh * nblk + r) * Kp : nullptr;
+
+    // stage the candidate rows (16-byte chunks, coalesced within a row) and the query rows
+    for (int c = tid; c < C * CH; c += 256) {
+        const int p = c / CH, part = c % CH;
+        const int64_t id = prow ? (int64_t)prow[p >> 4] * 16 + (p & 15) : p;
+        *reinterpret_cast<u32x4 *>(kc + p * STRIDE + part * 16) = *reinterpret_cast<const u32x4 *>(Kb + id * D + part * 8);
+    }
+    for (int c = tid; c < 16 * CH; c += 256) {
+        const int u = c / CH, part = c % CH;
+        const int64_t i = min(r * 16 + u, n_l - 1);          // rows past a ragged end are computed but not stored
+        *reinterpret_cast<u32x4 *>(qs + u * STRIDE + part * 16) =
+            *reinterpret_cast<const u32x4 *>(Ql + (bh * n_l + i) * D + part * 8);
+    }
+    __syncthreads();
+
+    const int cg = tid & 15, row = tid >> 4;                // 16 consecutive lanes share a query row
+    float sc[8];
+#pragma unroll
+    for (int m = 0; m < 8; ++m) sc[m] = 0.f;
+    for (int ch = 0; ch < CH; ++ch) {
+        float q[8];
+        unpack8(*reinterpret_cast<const u32x4 *>(qs + row * STRIDE + ch * 16), q);
+#pragma unroll
+        for (int m = 0; m < 8; ++m) {
+            const int p = min(cg + 16 * m, C - 1);
+            float k[8];
+            unpack8(*reinterpret_cast<const u32x4 *>(kc + p * STRIDE + ch * 16), k);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) sc[m] = __builtin_fmaf(q[e], k[e], sc[m]);
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < 8; ++m)
+        if (cg + 16 * m >= C) sc[m] = -INFINITY;
+
+    // K rounds of arg-max over the row's candidates (score descending, position ascending)
+    int mine = 0;                                           // lane k of the row group keeps the k-th winner
+    for (int k = 0; k < Kout; ++k) {
+        float bs = sc[0];
+        int bp = cg;
+#pragma unroll
+        for (int m = 1; m < 8; ++m)
+            if (sc[m] > bs) { bs = sc[m]; bp = cg + 16 * m; }   // ascending positions: strict '>' keeps the lowest
+#pragma unroll
+        for (int o = 8; o >= 1; o >>= 1) {
+            const float os = __shfl_xor(bs, o, 16);
+            const int op = __shfl_xor(bp, o, 16);
+            if (os > bs || (os == bs && op < bp)) { bs = os; bp = op; }
+        }
+#pragma unroll
+        for (int m = 0; m < 8; ++m)
+            if (bp == cg + 16 * m) sc[m] = -INFINITY;
+        if (cg == k) mine = bp;
+    }
+    // candidate positions ascend with key id (parent rows are ascending): rank the winners by position
+    int rank = 0;
+    for (int k = 0; k < Kout; ++k) rank += (__shfl(mine, k, 16) < mine) ? 1 : 0;
+    const int64_t i = r * 16 + row;
+    if (cg < Kout && i < n_l) {
+        const int64_t id = prow ? (int64_t)prow[mine >> 4] * 16 + (mine & 15) : mine;
+        out[(bh * n_l + i) * Kout + rank] = (int32_t)id;
+    }
+}
+
+// true if the fast kernel covers this level
+bool select_fast_ok(const Plan &p, int l) {
+    const int C = (l == p.L) ? (int)p.n[l] : p.Kl[l] * p.B;
+    return p.elt == 2 && p.B == 16 && (p.d == 64 || p.d == 128) && p.n[l] <= (int64_t)INT32_MAX && C <= 128 &&
+           p.Kl[l - 1] <= 16 && (l == p.L ? p.n[l] <= 128 : true);
+}
+
+hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s) {
+    const char *w = static_cast<const char *>(ws);
+    const bool top = (l == p.L);
+    const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
+    const int64_t nblk = (p.n[l] + 15) / 16;
+    const uint16_t *Ql = (const uint16_t *)(w + p.pyr_off[0][l]), *Kl = (const uint16_t *)(w + p.pyr_off[1][l]);
+    dim3 grid((unsigned)(p.bh * nblk));
+    if (p.d == 64)
+        select_fast_kernel<64><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], top ? nullptr : parent, top ? 0 : p.Kl[l], p.Kl[l - 1],
+                                                    out, C, nblk);
+    else
+        select_fast_kernel<128><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], top ? nullptr : parent, top ? 0 : p.Kl[l],
+                                                     p.Kl[l - 1], out, C, nblk);
+    return hipGetLastError();
+}
+
+}  // namespace llsa
