@@ -246,7 +246,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
     const int64_t nkb = a.n_l >> 4;                        // key blocks per head (a multiple of 4)
-    // plain order: hot key blocks cluster, and round-robin dispatch spreads a cluster over the XCDs
+    // The 16 key blocks under one level-1 token draw their queries from one pool (the fine blocks under the
+    // level-1 query blocks that listed that token), about 0.5 MB of Q and dO.  Keep the four workgroups of
+    // such a group on one XCD (ids congruent modulo 8) so the pool is fetched into one L2 only, and deal
+    // the groups round-robin over the XCDs so that clusters of hot key blocks are spread.
+    // (Measured: keeping such a group on one XCD does not pay; the plain order spreads hot clusters best.)
     const int64_t kb0 = (int64_t)blockIdx.x * 4;           // this workgroup's four key blocks (same head)
     const int64_t bh = kb0 / nkb;
 

@@ -108,9 +108,21 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
     }
     // MFMA kernels: bf16, B = 16, d = 64 / 128, and whole workgroups of 4 query blocks per head
     p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && d.B == 16 && (d.d == 64 || d.d == 128) && d.N % 64 == 0;
+    // coarse-level dK/dV grouped by level-1 query block: d = 64, whole groups of 256 queries, short lists
+    int coarse_blocks = 0;
+    for (int l = 1; l <= p.Le; ++l) coarse_blocks += (l < p.L) ? p.Kl[l] : (int)((p.n[l] + 15) / 16);
+    p.group = p.fast && d.d == 64 && d.N % 256 == 0 && p.Le >= 1 && coarse_blocks <= 512;
+    p.grp_slab_off = p.grp_red_off[0] = p.grp_red_off[1] = ws;
+    if (p.group) {
+        size_t slab = 0, red = 0;
+        dkv_group_sizes(p, &slab, &red);
+        p.grp_slab_off = ws;   ws = align_up(ws + slab);
+        p.grp_red_off[0] = ws; ws = align_up(ws + red);
+        p.grp_red_off[1] = ws; ws = align_up(ws + red);
+    }
     p.part_off = ws;
     p.part_bytes = 0;
-    if (p.fast)
+    if (p.fast && !p.group)
         for (int l = 1; l <= p.Le; ++l) {                  // split slabs of the key-major coarse-level kernels
             const size_t slab = (size_t)p.bh * ((p.n[l] + 15) / 16) * 16 * p.d * sizeof(float);
             const size_t need = 2 * slab * dkv_splits(p, l);
@@ -297,7 +309,8 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
     {
         StageScope sc(kDkvCoarse, call, s);
-        for (int l = p.Le; l >= 1; --l) {
+        if (p.group) LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s));
+        else for (int l = p.Le; l >= 1; --l) {
             if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
             else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
         }

@@ -26,6 +26,8 @@ struct Plan {
     size_t C_off[kMaxL], cnt_off[kMaxL], Iq_off[kMaxL], Iqtmp_off[kMaxL];
     size_t dKacc_off[kMaxL + 1], dVacc_off[kMaxL + 1]; // fp32 gradients of pooled level l (1..L)
     size_t part_off, part_bytes;    // partial sums of split key-major reductions
+    size_t grp_slab_off, grp_red_off[2];   // partials of the query-grouped coarse dK/dV kernel and its reductions
+    bool group;                     // coarse levels' dK/dV run grouped by level-1 query block
     size_t ws_fwd, ws_bwd;
     int list_len;                   // tokens one query attends to
     bool fast;                      // MFMA kernels apply (bf16, B = 16, d in {64, 128})
@@ -84,5 +86,9 @@ hipError_t launch_dq_shared(const Plan &p, const LevelTable &t, const void *Q, c
 hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO, const float *LSE,
                            const float *D, void *ws, void *dK, void *dV, hipStream_t s);
 int dkv_splits(const Plan &p, int l);    // workgroups sharing one key block's query list at level l
+// all coarse levels (Le .. 1) at once, grouped by level-1 query block; fills the levels' fp32 gradients
+hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
+                            const float *D, void *ws, hipStream_t s);
+void dkv_group_sizes(const Plan &p, size_t *slab_bytes, size_t *red_bytes);
 
 }  // namespace llsa
