@@ -171,16 +171,28 @@ __global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
         k = p[tid];
         v = p[256 + tid];
     } else {
+        // first every thread resolves one lister (query block row and the position of j in that row's list),
+        // 256 at a time, then all threads add the partials in list order with independent loads
+        __shared__ int64_t unit[256];
         const int32_t beg = a.C[bh * (a.rows + 1) + j], end = a.C[bh * (a.rows + 1) + j + 1];
         const int32_t *lst = a.Iq + bh * a.rows * a.Kl;
-        for (int32_t e = beg; e < end; ++e) {
-            const int64_t r = lst[e];
-            const int32_t *row = a.I + (bh * a.rows + r) * a.Kl;
-            int pos = 0;
-            for (int x = 0; x < a.Kl; ++x) pos += (row[x] < (int32_t)j) ? 1 : 0;   // rows are ascending
-            const f32x4 *p = part + ((bh * a.cnt + r) * a.nblk + pos) * (kUnit / 4);
-            k += p[tid];
-            v += p[256 + tid];
+        for (int32_t e0 = beg; e0 < end; e0 += 256) {
+            const int32_t m = min(256, end - e0);
+            __syncthreads();
+            if (tid < m) {
+                const int64_t r = lst[e0 + tid];
+                const int32_t *row = a.I + (bh * a.rows + r) * a.Kl;
+                int pos = 0;
+                for (int x = 0; x < a.Kl; ++x) pos += (row[x] < (int32_t)j) ? 1 : 0;   // rows are ascending
+                unit[tid] = ((bh * a.cnt + r) * a.nblk + pos) * (kUnit / 4);
+            }
+            __syncthreads();
+#pragma unroll 4
+            for (int32_t e = 0; e < m; ++e) {
+                const f32x4 *p = part + unit[e];
+                k += p[tid];
+                v += p[256 + tid];
+            }
         }
     }
     const int64_t tok = j * 16 + (tid >> 4);

@@ -378,48 +378,19 @@ __global__ void csc_fill_kernel(CscLevels a) {
     const int32_t slot = L.C[bh * (L.T + 1) + key] + atomicAdd(&L.cnt[bh * L.T + key], 1);
     L.Iq_tmp[bh * L.eph + slot] = (int32_t)(within / L.Kl);
 }
-// 16 lanes per key: rank-sort its list (entries are distinct query rows).  Lists of up to 16 entries are
-// ranked in registers; longer ones re-read the list from memory.
+// one thread per list entry: its rank among the entries of the same key (entries are distinct query rows)
+// is its place in the key's ascending list.  The unsorted list is re-read through the caches.
 __global__ void __launch_bounds__(256) csc_sort_kernel(CscLevels a) {
     const CscLevel &L = a.lv[blockIdx.y];
-    const int sub = threadIdx.x & 15;
-    int64_t key_flat = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);
-    const bool live = key_flat < L.nk;
-    if (!live) key_flat = L.nk - 1;
-    const int64_t bh = key_flat / L.T, key = key_flat % L.T;
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= L.total) return;
+    const int64_t bh = e / L.eph, within = e % L.eph;
+    const int32_t key = L.I[e], x = (int32_t)(within / L.Kl);
     const int32_t beg = L.C[bh * (L.T + 1) + key], end = L.C[bh * (L.T + 1) + key + 1];
     const int32_t *src = L.Iq_tmp + bh * L.eph;
-    int32_t *dst = L.Iq + bh * L.eph;
-    const int32_t n = live ? end - beg : 0;
-    if (n <= 16) {
-        const int32_t x = sub < n ? src[beg + sub] : 0x7fffffff;
-        int32_t rank = 0;
-#pragma unroll
-        for (int b = 0; b < 16; ++b) rank += (__shfl(x, b, 16) < x) ? 1 : 0;
-        if (sub < n) dst[beg + rank] = x;
-    }
-    // longer lists: the whole wave takes them one after the other
-    const int lane = threadIdx.x & 63;
-    for (int q = 0; q < 4; ++q) {
-        const int32_t nq = __builtin_amdgcn_readlane(n, q * 16), bq = __builtin_amdgcn_readlane(beg, q * 16);
-        if (nq <= 16) continue;
-        const int64_t bhq = ((int64_t)blockIdx.x * 16 + (threadIdx.x >> 6) * 4 + q) / L.T;   // that key's head
-        const int32_t *s2 = L.Iq_tmp + bhq * L.eph;
-        int32_t *d2 = L.Iq + bhq * L.eph;
-        if (nq <= 64) {
-            const int32_t x = lane < nq ? s2[bq + lane] : 0x7fffffff;
-            int32_t rank = 0;
-            for (int b = 0; b < nq; ++b) rank += (__builtin_amdgcn_readlane(x, b) < x) ? 1 : 0;
-            if (lane < nq) d2[bq + rank] = x;
-        } else {
-            for (int32_t i = lane; i < nq; i += 64) {
-                const int32_t x = s2[bq + i];
-                int32_t rank = 0;
-                for (int32_t b = 0; b < nq; ++b) rank += (s2[bq + b] < x) ? 1 : 0;
-                d2[bq + rank] = x;
-            }
-        }
-    }
+    int32_t rank = 0;
+    for (int32_t b = beg; b < end; ++b) rank += (src[b] < x) ? 1 : 0;
+    L.Iq[bh * L.eph + beg + rank] = x;
 }
 
 // Alg. 2 for levels 0 .. top (the levels whose lists the backward uses), five launches in all
@@ -447,7 +418,7 @@ hipError_t launch_csc(const Plan &p, int top, const int32_t *indices, void *ws, 
     csc_count_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
     csc_scan_kernel<<<dim3(p.bh, nl), 1024, 0, s>>>(a);
     csc_fill_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
-    csc_sort_kernel<<<dim3((unsigned)((max_nk + 15) / 16), nl), 256, 0, s>>>(a);
+    csc_sort_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
     return hipGetLastError();
 }
 
