@@ -29,8 +29,9 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
     return c.b;
 }
 
-template <int D>
-__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))) attn_fwd_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q,
+// NB = fine query blocks per wave (1 or 2); a workgroup owns 8 * NB consecutive blocks, all siblings
+template <int D, int NB>
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2))) attn_fwd_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q,
                                                                uint16_t *__restrict__ O, float *__restrict__ LSE,
                                                                int64_t N, int64_t total_wgs) {
     constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, PARTS = D / 8, TILE = 32 * STRIDE;
@@ -42,17 +43,17 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, g = lane >> 4;
-    const int64_t groups = N >> 8;                                    // sibling groups per head
+    const int64_t groups = N / (128 * NB);                            // workgroups per head
     const int64_t wg = xcd_contiguous(blockIdx.x, total_wgs);
-    const int64_t bh = wg / groups, blk0 = (wg % groups) * 16;
+    const int64_t bh = wg / groups, blk0 = (wg % groups) * (8 * NB);
     const float sc2 = t.scale * kLog2e;
 
-    bf16x8 qop[2][KS];
-    f32x4 acc[2][NT];
-    float m[2], lsum[2];
+    bf16x8 qop[NB][KS];
+    f32x4 acc[NB][NT];
+    float m[NB], lsum[NB];
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const uint16_t *qrow = Q + (bh * N + (blk0 + 2 * wave + b) * 16 + i16) * D + g * 8;
+    for (int b = 0; b < NB; ++b) {
+        const uint16_t *qrow = Q + (bh * N + (blk0 + NB * wave + b) * 16 + i16) * D + g * 8;
 #pragma unroll
         for (int s = 0; s < KS; ++s) qop[b][s] = ld_bf16x8(qrow + 32 * s);
 #pragma unroll
@@ -165,9 +166,9 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
                     kop[h][ks] = *reinterpret_cast<const bf16x8 *>(kt + (h * 16 + i16) * STRIDE + g * 16 + ks * 64);
-            f32x4 s[2][2];
+            f32x4 s[NB][2];
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     s[b][h] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -175,7 +176,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))
                     for (int ks = 0; ks < KS; ++ks) s[b][h] = mfma16(kop[h][ks], qop[b][ks], s[b][h]);
                 }
             softmax_pv(B0{}, s[0][0], s[0][1], cnt[0], cnt[1], bias2[0], bias2[1], vt);
-            softmax_pv(B1{}, s[1][0], s[1][1], cnt[0], cnt[1], bias2[0], bias2[1], vt);
+            if constexpr (NB > 1) softmax_pv(B1{}, s[NB - 1][0], s[NB - 1][1], cnt[0], cnt[1], bias2[0], bias2[1], vt);
         }
     }
 
@@ -190,7 +191,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))
     auto phase_b = [&](auto bsel) {
         constexpr int b = decltype(bsel)::value;
         BlockTable tab;
-        tab.fill(t, bh, blk0 + 2 * wave + b, 0, 0, lane, D, 1);       // level 0 only (K_0 <= 64 blocks)
+        tab.fill(t, bh, blk0 + NB * wave + b, 0, 0, lane, D, 1);      // level 0 only (K_0 <= 64 blocks)
         bf16x8 kop[2][KS];
         u32x4 vreg[VCH];
         auto load_tile = [&](int j0) {
@@ -226,14 +227,14 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))
         }
     };
     phase_b(B0{});
-    phase_b(B1{});
+    if constexpr (NB > 1) phase_b(B1{});
 
     // ------------------------------------------------------------------ epilogue
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < NB; ++b) {
         const float l = rows_sum(lsum[b]);
         const float inv = 1.f / l;
-        const int64_t row = bh * N + (blk0 + 2 * wave + b) * 16 + i16;
+        const int64_t row = bh * N + (blk0 + NB * wave + b) * 16 + i16;
         uint16_t *orow = O + row * D + 4 * g;
 #pragma unroll
         for (int n = 0; n < NT; ++n) {
@@ -248,10 +249,15 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4))
 
 hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                   hipStream_t s) {
-    const int64_t wgs = (int64_t)p.bh * (p.N / 256);
-    dim3 grid((unsigned)wgs);
-    if (p.d != 64) return hipErrorInvalidValue;       // d = 128 would need more than 64 KB of LDS per workgroup
-    attn_fwd_shared_kernel<64><<<grid, 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N, wgs);
+    if (p.d == 64) {                                  // two query blocks per wave: 16 per workgroup
+        const int64_t wgs = (int64_t)p.bh * (p.N / 256);
+        attn_fwd_shared_kernel<64, 2><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N,
+                                                                           wgs);
+    } else {                                          // d = 128: one query block per wave (registers), 8 per workgroup
+        const int64_t wgs = (int64_t)p.bh * (p.N / 128);
+        attn_fwd_shared_kernel<128, 1><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE,
+                                                                            p.N, wgs);
+    }
     return hipGetLastError();
 }
 

@@ -26,7 +26,7 @@ __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 
 
 // NB = fine query blocks per wave (1 or 2); a workgroup owns 8 * NB consecutive blocks, all siblings
 template <int D, int NB>
-__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(4, 4)))
+__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2)))
 dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *__restrict__ O,
                  const uint16_t *__restrict__ dO, const float *__restrict__ LSE, float *__restrict__ Dsum,
                  uint16_t *__restrict__ dQ, int64_t N, int64_t total_wgs) {
@@ -238,7 +238,11 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
 hipError_t launch_dq_shared(const Plan &p, const LevelTable &t, const void *Q, const void *O, const void *dO,
                             const float *LSE, float *D, void *dQ, hipStream_t s) {
     const int64_t wgs = (int64_t)p.bh * (p.N / 128);                  // one query block per wave: 8 per workgroup
-    if (p.d != 64) return hipErrorInvalidValue;
+    if (p.d == 128) {
+        dq_shared_kernel<128, 1><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (const uint16_t *)O,
+                                                                      (const uint16_t *)dO, LSE, D, (uint16_t *)dQ, p.N, wgs);
+        return hipGetLastError();
+    }
     dq_shared_kernel<64, 1><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (const uint16_t *)O,
                                                              (const uint16_t *)dO, LSE, D, (uint16_t *)dQ, p.N, wgs);
     return hipGetLastError();

@@ -1,10 +1,10 @@
 // Hierarchical Top-K selection, one level (Alg. 1, selection loop), fast path for bf16, B = 16, at most
-// 128 candidates per query block and K <= 16.
+// 256 candidates per query block and K <= 16.
 //
 // One workgroup (256 threads) per level-l query block of 16 query tokens.  The candidate key rows (all
 // n_L tokens at the coarsest level, the 16 * K_l children of the parent's picks below it) and the 16
 // query rows are staged once in LDS; lane (row r, column group c) scores candidates c, c + 16, ... of
-// row r, so the 128 scores of a row sit in one 16-lane row group and the Top-K runs in registers.
+// row r, so all scores of a row sit in one 16-lane row group and the Top-K runs in registers.
 // Scores are fp32 fused-multiply-add chains over channels 0 .. d-1 in order (the same chain on every
 // launch shape), ties go to the lower key id, rows are written in ascending id order.
 #include "mfma_common.h"
@@ -19,13 +19,14 @@ __device__ __forceinline__ void unpack8(u32x4 w, float *f) {
     }
 }
 
-template <int D>
+// MC = candidates per lane (8: up to 128 candidates, 16: up to 256)
+template <int D, int MC>
 __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
                                                            int64_t n_l, const int32_t *__restrict__ parent, int Kp,
                                                            int Kout, int32_t *__restrict__ out, int C, int64_t nblk) {
     constexpr int STRIDE = 2 * D + 16;                      // bytes per staged row: keeps 16-byte reads conflict-free
     constexpr int CH = D / 8;                               // 16-byte chunks per row
-    __shared__ __attribute__((aligned(16))) char kc[128 * STRIDE];
+    __shared__ __attribute__((aligned(16))) char kc[16 * MC * STRIDE];
     __shared__ __attribute__((aligned(16))) char qs[16 * STRIDE];
 
     const int tid = threadIdx.x;
@@ -48,14 +49,14 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
     __syncthreads();
 
     const int cg = tid & 15, row = tid >> 4;                // 16 consecutive lanes share a query row
-    float sc[8];
+    float sc[MC];
 #pragma unroll
-    for (int m = 0; m < 8; ++m) sc[m] = 0.f;
+    for (int m = 0; m < MC; ++m) sc[m] = 0.f;
     for (int ch = 0; ch < CH; ++ch) {
         float q[8];
         unpack8(*reinterpret_cast<const u32x4 *>(qs + row * STRIDE + ch * 16), q);
 #pragma unroll
-        for (int m = 0; m < 8; ++m) {
+        for (int m = 0; m < MC; ++m) {
             const int p = min(cg + 16 * m, C - 1);
             float k[8];
             unpack8(*reinterpret_cast<const u32x4 *>(kc + p * STRIDE + ch * 16), k);
@@ -64,7 +65,7 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
         }
     }
 #pragma unroll
-    for (int m = 0; m < 8; ++m)
+    for (int m = 0; m < MC; ++m)
         if (cg + 16 * m >= C) sc[m] = -INFINITY;
 
     // K rounds of arg-max over the row's candidates (score descending, position ascending)
@@ -73,7 +74,7 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
         float bs = sc[0];
         int bp = cg;
 #pragma unroll
-        for (int m = 1; m < 8; ++m)
+        for (int m = 1; m < MC; ++m)
             if (sc[m] > bs) { bs = sc[m]; bp = cg + 16 * m; }   // ascending positions: strict '>' keeps the lowest
 #pragma unroll
         for (int o = 8; o >= 1; o >>= 1) {
@@ -82,7 +83,7 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
             if (os > bs || (os == bs && op < bp)) { bs = os; bp = op; }
         }
 #pragma unroll
-        for (int m = 0; m < 8; ++m)
+        for (int m = 0; m < MC; ++m)
             if (bp == cg + 16 * m) sc[m] = -INFINITY;
         if (cg == k) mine = bp;
     }
@@ -98,9 +99,8 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
 
 // true if the fast kernel covers this level
 bool select_fast_ok(const Plan &p, int l) {
-    const int C = (l == p.L) ? (int)p.n[l] : p.Kl[l] * p.B;
-    return p.elt == 2 && p.B == 16 && (p.d == 64 || p.d == 128) && p.n[l] <= (int64_t)INT32_MAX && C <= 128 &&
-           p.Kl[l - 1] <= 16 && (l == p.L ? p.n[l] <= 128 : true);
+    const int64_t C = (l == p.L) ? p.n[l] : (int64_t)p.Kl[l] * p.B;
+    return p.elt == 2 && p.B == 16 && (p.d == 64 || p.d == 128) && C <= 256 && p.Kl[l - 1] <= 16;
 }
 
 hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s) {
@@ -109,13 +109,16 @@ hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_
     const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
     const int64_t nblk = (p.n[l] + 15) / 16;
     const uint16_t *Ql = (const uint16_t *)(w + p.pyr_off[0][l]), *Kl = (const uint16_t *)(w + p.pyr_off[1][l]);
+    const int32_t *par = top ? nullptr : parent;
+    const int Kp = top ? 0 : p.Kl[l], Kout = p.Kl[l - 1];
     dim3 grid((unsigned)(p.bh * nblk));
-    if (p.d == 64)
-        select_fast_kernel<64><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], top ? nullptr : parent, top ? 0 : p.Kl[l], p.Kl[l - 1],
-                                                    out, C, nblk);
-    else
-        select_fast_kernel<128><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], top ? nullptr : parent, top ? 0 : p.Kl[l],
-                                                     p.Kl[l - 1], out, C, nblk);
+    if (p.d == 64) {
+        if (C <= 128) select_fast_kernel<64, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
+        else select_fast_kernel<64, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
+    } else {
+        if (C <= 128) select_fast_kernel<128, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
+        else select_fast_kernel<128, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
+    }
     return hipGetLastError();
 }
 
