@@ -60,6 +60,19 @@ def cpu_baseline(cfg, x, threads):
                       f"one head per thread, {dt:.1f} s"}
 
 
+def measured_traffic(stage, workload, kind):
+    """HBM bytes per launch of a stage's kernel as measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by
+    the plain-copy calibration) and recorded in profiles/hbm_traffic.txt; None if that workload was not measured."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 5 and not line.startswith("#") and f[0] == stage and f[1] == workload and f[2] == kind:
+            return float(f[3]) + float(f[4])
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +86,9 @@ def main():
     ap.add_argument("--all-stages", action="store_true", help="after the timed region, one more pass timing every stage")
     ap.add_argument("--dense-compare", action="store_true", help="also time dense bf16 SDPA (forward) on this GPU")
     ap.add_argument("--force-generic", action="store_true", help="run the portable scalar kernels")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays of the step")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a plain device copy of 512 MiB (to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -84,6 +100,14 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.calibrate_copy:
+        src = torch.zeros(512 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel(), "copy_bytes_written": dst.numel(), "copies": 3}))
+        return
     llsa.load()                                               # fails loudly if the HIP library is not built
 
     cfg = dict(inputs.CONFIGS[args.config])
@@ -124,16 +148,37 @@ def main():
     fwd_flops, bwd_flops = algorithmic_flops(cfg, M)
     stage = "dkv_fine" if args.stage == "auto" else args.stage
 
-    llsa.stage_timing_begin(stage, max_calls=args.steps)      # two events per step around ONE kernel
+    # Eager pass: K steps with two HIP events per step around ONE kernel (the roofline kernel).
+    llsa.stage_timing_begin(stage, max_calls=args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
     st = llsa.stage_timing_end()
-    ms_per_step = dt / args.steps * 1e3
     kern_ms = st[stage][0] / max(st[stage][1], 1)
+    ms_per_step, mode = eager_ms, "eager launches"
+
+    # The library neither allocates nor synchronises, so a whole step can be replayed from a HIP graph, which
+    # removes the host launch gaps between its ~25 kernels.  Same kernels, same buffers, K replays timed.
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        for _ in range(max(1, args.warmup)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        ms_per_step, mode = (time.perf_counter() - t0) / args.steps * 1e3, "HIP graph replay of one step"
 
     # algorithmic work of one launch of the bracketed kernel
     bhNd = cfg["batch"] * cfg["heads"] * cfg["N"] * cfg["d"]
@@ -152,7 +197,7 @@ def main():
         roof_bound, peak, unit = ("mfma", PEAK_BF16_TFLOPS, "TFLOP/s") if bound == "mfma" else ("hbm", PEAK_HBM_GBPS, "GB/s")
     achieved = amount / (kern_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9) if kern_ms > 0 else 0.0
     roofline = {"kernel": stage, "bound": roof_bound, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": None, "kernel_ms": kern_ms}
+                "frac": achieved / peak, "traffic": measured_traffic(stage, cfg["name"], cfg["kind"]), "kernel_ms": kern_ms}
 
     out = {
         "metric": "llsa_fwd_bwd_effective_tflops_n65536_h16_d64_bf16" if args.config == 3 else
@@ -164,7 +209,8 @@ def main():
         "config": {"workload": f"BASELINE configs[{args.config}] {cfg['name']}: batch {cfg['batch']}, heads {cfg['heads']}, "
                                f"d {cfg['d']}, N {cfg['N']}, B {cfg['B']}, K {cfg['K']}, L {cfg['L']}, Le {cfg['L']}, "
                                f"{cfg['kind']} inputs, forward+backward",
-                   "gathered_tokens_per_query": M, "kernels": "generic" if args.force_generic else "default"},
+                   "gathered_tokens_per_query": M, "kernels": "generic" if args.force_generic else "default",
+                   "launch": mode, "eager_ms_per_step": eager_ms},
         "roofline": roofline,
     }
 

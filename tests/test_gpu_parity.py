@@ -151,3 +151,40 @@ def test_backward_repool_matches_reuse():
     dQ, dK, dV = llsa.backward(plan, Q, K, V, a["O"], a["LSE"], a["indices"], dO, ws)
     torch.cuda.synchronize()
     assert torch.equal(dQ, a["dQ"]) and torch.equal(dK, a["dK"]) and torch.equal(dV, a["dV"])
+
+
+def test_hip_graph_replays_match_eager():
+    """The library never allocates or synchronises, so a forward+backward step can be captured in a HIP graph;
+    every replay (with eager work and synchronisations in between) must reproduce the eager results bit for bit."""
+    cfg = dict(name="graph", batch=1, heads=4, d=64, N=4096, B=16, K=8, L=2, dtype="bf16", kind="smooth")
+    x = H.make_inputs(cfg, 31)
+    plan = H.make_plan(cfg)
+    Q, K, V, dO = (H.to_dev(x[n], cfg) for n in ("Q", "K", "V", "dO"))
+    ws, idx = plan.alloc_workspace(True), plan.alloc_indices()
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    LSE = torch.empty(1, 4, 4096, dtype=torch.float32, device="cuda")
+
+    def step():
+        llsa.forward(plan, Q, K, V, O, LSE, idx, ws)
+        llsa.backward(plan, Q, K, V, O, LSE, idx, dO, ws, dQ, dK, dV)
+
+    step()
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (O, LSE, idx, dQ, dK, dV)]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(4):
+        for t in (O, LSE, dQ, dK, dV):
+            t.zero_()
+        idx.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, want in zip(("O", "LSE", "indices", "dQ", "dK", "dV"), (O, LSE, idx, dQ, dK, dV), ref):
+            assert torch.equal(got, want), f"replay {rep}: {name} differs from the eager result"
