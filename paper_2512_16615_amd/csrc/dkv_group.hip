@@ -28,6 +28,7 @@ struct GroupArgs {
     int64_t lvl_off[kMaxL + 1];                         // float offset of level l's partials [R][pos][kUnit]
     int nblk[kMaxL + 1];                                // key blocks of level l in a list
     int64_t N, NR;                                      // NR = level-1 query blocks per head
+    int lev_end;                                        // levels 1 .. lev_end - 1 are processed here
     float sc2, scale;
 };
 
@@ -69,11 +70,12 @@ dkv_group_kernel(LevelTable t, GroupArgs a) {
     for (int n = 0; n < NT; ++n)
         troff[n] = (4 * g + (i16 >> 2)) * 128 + (((2 * n + ((i16 >> 1) & 1)) ^ key_tr) << 4) + ((i16 & 1) << 3);
 
-    const int c_begin = t.bseg[1], nbc = t.bseg[t.nlev] - c_begin;
+    const int nlev = min(t.nlev, a.lev_end);
+    const int c_begin = t.bseg[1], nbc = pick(t.bseg, nlev) - c_begin;
     BlockTable ctab;
     int chunk = -1;
     for (int jb = wave; jb < nbc; jb += 8) {
-        if ((jb >> 6) != chunk) { chunk = jb >> 6; ctab.fill(t, bh, Rh * 16, c_begin, chunk, lane, D); }
+        if ((jb >> 6) != chunk) { chunk = jb >> 6; ctab.fill(t, bh, Rh * 16, c_begin, chunk, lane, D, nlev); }
         const char *kp = ctab.K(jb & 63), *vp = ctab.V(jb & 63);
         const int cnt = ctab.count(jb & 63);
         const float bias2 = ctab.bias(jb & 63);
@@ -124,7 +126,7 @@ dkv_group_kernel(LevelTable t, GroupArgs a) {
         const int jl = jb + c_begin;
         int l = 1;
 #pragma unroll
-        for (int x = 2; x <= kMaxL; ++x) l += (x < t.nlev && jl >= t.bseg[x]) ? 1 : 0;
+        for (int x = 2; x <= kMaxL; ++x) l += (x < nlev && jl >= t.bseg[x]) ? 1 : 0;
         const int pos = jl - pick(t.bseg, l);
         float *dst = a.slab + pick(a.lvl_off, l) + ((int64_t)R * pick(a.nblk, l) + pos) * kUnit + i16 * D + 4 * g;
 #pragma unroll
@@ -207,11 +209,16 @@ __global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
     *reinterpret_cast<f32x4 *>(a.dstV + (bh * a.n_l + tok) * 64 + col) = v;
 }
 
+// Highest level the grouped kernel takes; levels above it (none at present) go to the split key-major kernel.
+// Sending a coarsest level of a single key block to the split kernel, to spare the 8 waves a third round for
+// one block, was measured slower (the split kernel re-reads every Q / dO row).
+int dkv_group_top(const Plan &p) { return p.Le; }
+
 // bytes of the partial slab and of each of the two reduction buffers
 void dkv_group_sizes(const Plan &p, size_t *slab_bytes, size_t *red_bytes) {
     const int64_t NR = p.N / 256;
     size_t slab = 0, red = 0;
-    for (int l = 1; l <= p.Le; ++l) {
+    for (int l = 1; l <= dkv_group_top(p); ++l) {
         const int64_t nblk = l < p.L ? p.Kl[l] : (p.n[l] + 15) / 16;
         const size_t lv = (size_t)p.bh * NR * nblk * kUnit * sizeof(float);
         slab += lv;
@@ -232,8 +239,10 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
     a.N = p.N; a.NR = NR;
     a.sc2 = p.scale * kLog2e; a.scale = p.scale;
     int64_t off = 0;
+    const int top = dkv_group_top(p);
+    a.lev_end = top + 1;
     for (int l = 0; l <= kMaxL; ++l) { a.lvl_off[l] = 0; a.nblk[l] = 0; }
-    for (int l = 1; l <= p.Le; ++l) {
+    for (int l = 1; l <= top; ++l) {
         a.nblk[l] = l < p.L ? p.Kl[l] : (int)((p.n[l] + 15) / 16);
         a.lvl_off[l] = off;
         off += (int64_t)p.bh * NR * a.nblk[l] * kUnit;
@@ -243,7 +252,7 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
     if (e != hipSuccess) return e;
 
     float *red[2] = {(float *)(w + p.grp_red_off[0]), (float *)(w + p.grp_red_off[1])};
-    for (int l = p.Le; l >= 1; --l) {                       // top-down: a level adds the share of the one above
+    for (int l = top; l >= 1; --l) {                        // top-down: a level adds the share of the one above
         const bool dense = (l == p.L);
         const float *cur = a.slab + a.lvl_off[l];
         int64_t cnt = NR;

@@ -111,7 +111,7 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
     // coarse-level dK/dV grouped by level-1 query block: d = 64, whole groups of 256 queries, short lists
     int coarse_blocks = 0;
     for (int l = 1; l <= p.Le; ++l) coarse_blocks += (l < p.L) ? p.Kl[l] : (int)((p.n[l] + 15) / 16);
-    p.group = p.fast && d.d == 64 && d.N % 256 == 0 && p.Le >= 1 && coarse_blocks <= 512;
+    p.group = p.fast && d.d == 64 && d.N % 256 == 0 && p.Le >= 1 && coarse_blocks <= 512 && dkv_group_top(p) >= 1;
     p.grp_slab_off = p.grp_red_off[0] = p.grp_red_off[1] = ws;
     if (p.group) {
         size_t slab = 0, red = 0;
@@ -122,8 +122,8 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
     }
     p.part_off = ws;
     p.part_bytes = 0;
-    if (p.fast && !p.group)
-        for (int l = 1; l <= p.Le; ++l) {                  // split slabs of the key-major coarse-level kernels
+    if (p.fast)
+        for (int l = p.group ? dkv_group_top(p) + 1 : 1; l <= p.Le; ++l) {   // split slabs of the key-major kernels
             const size_t slab = (size_t)p.bh * ((p.n[l] + 15) / 16) * 16 * p.d * sizeof(float);
             const size_t need = 2 * slab * dkv_splits(p, l);
             if (need > p.part_bytes) p.part_bytes = need;
@@ -309,8 +309,10 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
     {
         StageScope sc(kDkvCoarse, call, s);
-        if (p.group) LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s));
-        else for (int l = p.Le; l >= 1; --l) {
+        if (p.group) {                                      // levels above the grouped kernel's range first
+            for (int l = p.Le; l > dkv_group_top(p); --l) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+            LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s));
+        } else for (int l = p.Le; l >= 1; --l) {
             if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
             else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
         }

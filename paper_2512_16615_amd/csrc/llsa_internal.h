@@ -90,5 +90,6 @@ int dkv_splits(const Plan &p, int l);    // workgroups sharing one key block's q
 hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
                             const float *D, void *ws, hipStream_t s);
 void dkv_group_sizes(const Plan &p, size_t *slab_bytes, size_t *red_bytes);
+int dkv_group_top(const Plan &p);         // highest level the grouped kernel takes (the rest: split kernel)
 
 }  // namespace llsa
