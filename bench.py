@@ -11,6 +11,9 @@ fp32 accumulation, smooth-field Q/K/V (the pixel-grid stand-in for DiT activatio
 
 Prints ONE JSON line.  `value` is effective TFLOP/s = algorithmic sparse FLOPs of forward + backward
 (4 d M N b h for the forward, 2.5 x that for the backward; M = gathered tokens per query) / step time.
+
+`--sweep n|L|Le|K|all` instead runs the same kernels over other shapes (sequence length at fixed head
+geometry, number of levels, enrichment depth, Top-K) and prints one JSON line per case plus a table on stderr.
 """
 from __future__ import annotations
 
@@ -73,6 +76,160 @@ def measured_traffic(stage, workload, kind):
     return None
 
 
+def device_inputs(cfg, seed, threads=16, keep_host=False):
+    """Seeded synthetic Q, K, V, dO on the GPU in the I/O type (and, if asked, the same rounded values on the host)."""
+    import torch
+    from paper_2512_16615_amd import inputs
+    bf16 = cfg["dtype"] == "bf16"
+    shape = (cfg["batch"], cfg["heads"], cfg["N"], cfg["d"])
+    dev = {n: torch.empty(shape, dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda")
+           for n in ("Q", "K", "V", "dO")}
+    jobs = [(n, b, h) for n in dev for b in range(cfg["batch"]) for h in range(cfg["heads"])]
+
+    def one(job):
+        n, b, h = job
+        return job, inputs.make_head(cfg["kind"], seed, n, b, h, cfg["N"], cfg["d"])
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for (n, b, h), v in ex.map(one, jobs):
+            dev[n][b, h].copy_(torch.from_numpy(v))          # rounds to nearest even for bf16 I/O
+    host = {n: dev[n].float().cpu().numpy() for n in dev} if keep_host else None
+    return dev, host
+
+
+def timed(fn, steps, warmup, graph):
+    """Milliseconds per call of fn (which only enqueues work): eager launches, then optionally replays of a HIP
+    graph holding one call.  Returns (eager_ms, graph_ms or None)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    eager = (time.perf_counter() - t0) / steps * 1e3
+    if not graph:
+        return eager, None
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        fn()
+        with torch.cuda.graph(g, stream=side):
+            fn()
+    torch.cuda.current_stream().wait_stream(side)
+    for _ in range(max(1, warmup)):
+        g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        g.replay()
+    torch.cuda.synchronize()
+    return eager, (time.perf_counter() - t0) / steps * 1e3
+
+
+class Case:
+    """Plan and buffers of one workload; step() enqueues forward + backward."""
+
+    def __init__(self, cfg, dev, Le=None, force_generic=False):
+        import torch
+        from paper_2512_16615_amd import llsa
+        self.llsa, self.cfg = llsa, cfg
+        bf16 = cfg["dtype"] == "bf16"
+        self.plan = llsa.Plan(cfg["batch"], cfg["heads"], cfg["N"], cfg["d"], cfg["B"], cfg["K"], cfg["L"], Le=Le,
+                              dtype=llsa.BF16 if bf16 else llsa.F32, kernel_path=1 if force_generic else 0)
+        self.Le = cfg["L"] if Le is None else Le
+        self.ws = self.plan.alloc_workspace(True)
+        self.idx = self.plan.alloc_indices()
+        self.Q, self.K, self.V, self.dO = dev["Q"], dev["K"], dev["V"], dev["dO"]
+        self.O = torch.empty_like(self.Q)
+        self.LSE = torch.empty(cfg["batch"], cfg["heads"], cfg["N"], dtype=torch.float32, device="cuda")
+        self.dQ, self.dK, self.dV = torch.empty_like(self.Q), torch.empty_like(self.Q), torch.empty_like(self.Q)
+        # gathered tokens per query: K_l * B of every enriched sparse level, all n_L tokens if the top is enriched
+        self.M = sum(li.K_l * cfg["B"] for l, li in enumerate(self.plan.levels) if l <= self.Le)
+        if self.Le == cfg["L"]:
+            self.M += cfg["N"] // cfg["B"] ** cfg["L"]
+
+    def forward(self):
+        self.llsa.forward(self.plan, self.Q, self.K, self.V, self.O, self.LSE, self.idx, self.ws)
+
+    def step(self):
+        self.forward()
+        self.llsa.backward(self.plan, self.Q, self.K, self.V, self.O, self.LSE, self.idx, self.dO, self.ws,
+                           self.dQ, self.dK, self.dV)
+
+    def stages(self, steps):
+        import torch
+        self.llsa.stage_timing_begin(-1, max_calls=steps)
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        return {k: (v[0] / v[1] if v[1] else None) for k, v in self.llsa.stage_timing_end().items()}
+
+
+def sweep_cases(which):
+    base = dict(batch=1, d=64, B=16, K=8, dtype="bf16", kind="smooth")
+    heads_for = {4096: 16, 16384: 16, 65536: 16, 262144: 8, 1048576: 4}     # distinct heads; throughput is per token
+    deepest = {4096: 2, 16384: 3, 65536: 3, 262144: 4, 1048576: 4}          # L = ceil(log_B N) - 1
+    out = []
+
+    def add(group, N, L, Le=None, K=8):
+        out.append((group, dict(base, name=f"{group}_N{N}_L{L}_Le{L if Le is None else Le}_K{K}", N=N, L=L, K=K,
+                                heads=heads_for[N]), Le))
+
+    if which in ("n", "all"):
+        for N in (4096, 16384, 65536, 262144, 1048576):
+            add("n", N, deepest[N])
+    if which in ("L", "all"):
+        for N, Ls in ((65536, (1, 2, 3)), (262144, (2, 3, 4))):
+            for L in Ls:
+                add("L", N, L)
+    if which in ("Le", "all"):
+        for Le in (0, 1, 2, 3):
+            add("Le", 65536, 3, Le=Le)
+    if which in ("K", "all"):
+        for K in (4, 8, 16, 32):
+            add("K", 65536, 3, K=K)
+    return out
+
+
+def run_sweep(args):
+    import torch
+    rows, cache = [], {}
+    for group, cfg, Le in sweep_cases(args.sweep):
+        key = (cfg["N"], cfg["heads"])
+        if key not in cache:                                   # the inputs depend on the shape only
+            cache.clear()
+            torch.cuda.empty_cache()
+            t0 = time.time()
+            cache[key] = device_inputs(cfg, 0x115A1000 + cfg["N"] % 9973)[0]
+            print(f"[sweep] inputs N={cfg['N']} heads={cfg['heads']} ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
+        case = Case(cfg, cache[key], Le=Le)
+        steps = max(3, min(args.steps, int(2e8 // (cfg["N"] * cfg["heads"])) + 3))
+        f_eager, f_graph = timed(case.forward, steps, args.warmup, not args.no_graph)
+        s_eager, s_graph = timed(case.step, steps, args.warmup, not args.no_graph)
+        fwd_ms, step_ms = (f_graph or f_eager), (s_graph or s_eager)
+        fwd_flops, bwd_flops = algorithmic_flops(cfg, case.M)
+        st = case.stages(steps)
+        row = {"case": cfg["name"], "group": group, "N": cfg["N"], "heads": cfg["heads"], "d": cfg["d"], "B": cfg["B"],
+               "K": cfg["K"], "L": cfg["L"], "Le": case.Le, "gathered_tokens_per_query": case.M, "steps": steps,
+               "fwd_ms": fwd_ms, "fwd_bwd_ms": step_ms, "eager_fwd_bwd_ms": s_eager,
+               "fwd_tflops": fwd_flops / fwd_ms / 1e9, "fwd_bwd_tflops": (fwd_flops + bwd_flops) / step_ms / 1e9,
+               "fwd_bwd_mtokens_per_s": cfg["N"] * cfg["heads"] / step_ms / 1e3,
+               "kv_backward_ms": (st.get("dkv_coarse") or 0.0) + (st.get("dkv_fine") or 0.0) + (st.get("index_transpose") or 0.0),
+               "stages_ms": st}
+        row["kv_backward_mtokens_per_s"] = cfg["N"] * cfg["heads"] / row["kv_backward_ms"] / 1e3
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+        del case
+    hdr = f"{'case':34s} {'M':>5s} {'fwd ms':>9s} {'f+b ms':>9s} {'fwd TF/s':>9s} {'f+b TF/s':>9s} {'f+b Mtok/s':>11s} {'KV-bwd Mtok/s':>14s}"
+    print(hdr, file=sys.stderr)
+    for r in rows:
+        print(f"{r['case']:34s} {r['gathered_tokens_per_query']:5d} {r['fwd_ms']:9.3f} {r['fwd_bwd_ms']:9.3f} {r['fwd_tflops']:9.1f} "
+              f"{r['fwd_bwd_tflops']:9.1f} {r['fwd_bwd_mtokens_per_s']:11.1f} {r['kv_backward_mtokens_per_s']:14.1f}", file=sys.stderr)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +246,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays of the step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 512 MiB (to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--sweep", default=None, choices=["n", "L", "Le", "K", "all"],
+                    help="run the shape sweep instead of the headline workload")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -109,43 +268,23 @@ def main():
         print(json.dumps({"copy_bytes_read": src.numel(), "copy_bytes_written": dst.numel(), "copies": 3}))
         return
     llsa.load()                                               # fails loudly if the HIP library is not built
+    if args.sweep:
+        run_sweep(args)
+        return
 
     cfg = dict(inputs.CONFIGS[args.config])
     if args.kind:
         cfg["kind"] = args.kind
-    seed = inputs.config_seed(args.config)
-    t0 = time.time()
-    x = {}
-    with ThreadPoolExecutor(max_workers=4) as ex:
-        futs = {n: ex.submit(inputs.make_tensor, cfg["kind"], seed, n, cfg["batch"], cfg["heads"], cfg["N"], cfg["d"])
-                for n in ("Q", "K", "V", "dO")}
-        for n, f in futs.items():
-            x[n] = f.result()
     bf16 = cfg["dtype"] == "bf16"
-    dev = {n: (torch.from_numpy(v).cuda().to(torch.bfloat16) if bf16 else torch.from_numpy(v).cuda()) for n, v in x.items()}
-    if bf16:                                                  # the oracle leg must see the rounded values
-        x = {n: dev[n].float().cpu().numpy() for n in x}
+    t0 = time.time()
+    dev, x = device_inputs(cfg, inputs.config_seed(args.config), keep_host=not args.no_cpu)
     print(f"[bench] inputs ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 
-    plan = llsa.Plan(cfg["batch"], cfg["heads"], cfg["N"], cfg["d"], cfg["B"], cfg["K"], cfg["L"],
-                     Le=args.Le, dtype=llsa.BF16 if bf16 else llsa.F32, kernel_path=1 if args.force_generic else 0)
-    ws = plan.alloc_workspace(True)
-    idx = plan.alloc_indices()
-    Q, K, V, dO = dev["Q"], dev["K"], dev["V"], dev["dO"]
-    O = torch.empty_like(Q)
-    LSE = torch.empty(cfg["batch"], cfg["heads"], cfg["N"], dtype=torch.float32, device="cuda")
-    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
-
-    def step():
-        llsa.forward(plan, Q, K, V, O, LSE, idx, ws)
-        llsa.backward(plan, Q, K, V, O, LSE, idx, dO, ws, dQ, dK, dV)
-
+    case = Case(cfg, dev, Le=args.Le, force_generic=args.force_generic)
     for _ in range(args.warmup):
-        step()
+        case.step()
     torch.cuda.synchronize()
-
-    M = sum(li.K_l * cfg["B"] for li in plan.levels) + cfg["N"] // cfg["B"] ** cfg["L"]
-    fwd_flops, bwd_flops = algorithmic_flops(cfg, M)
+    fwd_flops, bwd_flops = algorithmic_flops(cfg, case.M)
     stage = "dkv_fine" if args.stage == "auto" else args.stage
 
     # Eager pass: K steps with two HIP events per step around ONE kernel (the roofline kernel).
@@ -153,7 +292,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        case.step()
     torch.cuda.synchronize()
     eager_ms = (time.perf_counter() - t0) / args.steps * 1e3
     st = llsa.stage_timing_end()
@@ -163,27 +302,13 @@ def main():
     # The library neither allocates nor synchronises, so a whole step can be replayed from a HIP graph, which
     # removes the host launch gaps between its ~25 kernels.  Same kernels, same buffers, K replays timed.
     if not args.no_graph:
-        graph = torch.cuda.CUDAGraph()
-        side = torch.cuda.Stream()
-        side.wait_stream(torch.cuda.current_stream())
-        with torch.cuda.stream(side):
-            step()
-            with torch.cuda.graph(graph, stream=side):
-                step()
-        torch.cuda.current_stream().wait_stream(side)
-        for _ in range(max(1, args.warmup)):
-            graph.replay()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            graph.replay()
-        torch.cuda.synchronize()
-        ms_per_step, mode = (time.perf_counter() - t0) / args.steps * 1e3, "HIP graph replay of one step"
+        _, ms_per_step = timed(case.step, args.steps, 0, True)
+        mode = "HIP graph replay of one step"
 
     # algorithmic work of one launch of the bracketed kernel
     bhNd = cfg["batch"] * cfg["heads"] * cfg["N"] * cfg["d"]
     elt = 2 if bf16 else 4
-    per_level_pairs = 2.0 * cfg["d"] * cfg["N"] * cfg["batch"] * cfg["heads"] * (plan.levels[0].K_l * cfg["B"])
+    per_level_pairs = 2.0 * cfg["d"] * cfg["N"] * cfg["batch"] * cfg["heads"] * (case.plan.levels[0].K_l * cfg["B"])
     work = {  # stage -> (bound, algorithmic flops or bytes of one launch)
         "attn_fwd": ("mfma", fwd_flops),
         "dq": ("mfma", 1.5 * fwd_flops),                      # S, dP, dQ = dS K: three contractions over the list
@@ -207,28 +332,24 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"BASELINE configs[{args.config}] {cfg['name']}: batch {cfg['batch']}, heads {cfg['heads']}, "
-                               f"d {cfg['d']}, N {cfg['N']}, B {cfg['B']}, K {cfg['K']}, L {cfg['L']}, Le {cfg['L']}, "
+                               f"d {cfg['d']}, N {cfg['N']}, B {cfg['B']}, K {cfg['K']}, L {cfg['L']}, Le {case.Le}, "
                                f"{cfg['kind']} inputs, forward+backward",
-                   "gathered_tokens_per_query": M, "kernels": "generic" if args.force_generic else "default",
+                   "gathered_tokens_per_query": case.M, "kernels": "generic" if args.force_generic else "default",
                    "launch": mode, "eager_ms_per_step": eager_ms},
         "roofline": roofline,
     }
 
     if args.all_stages:
-        llsa.stage_timing_begin(-1, max_calls=args.steps)
-        for _ in range(args.steps):
-            step()
-        torch.cuda.synchronize()
-        out["stages_ms"] = {k: (v[0] / v[1] if v[1] else None) for k, v in llsa.stage_timing_end().items()}
+        out["stages_ms"] = case.stages(args.steps)
 
     if args.dense_compare:
         import torch.nn.functional as F
         for _ in range(2):
-            F.scaled_dot_product_attention(Q, K, V)
+            F.scaled_dot_product_attention(case.Q, case.K, case.V)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(3):
-            F.scaled_dot_product_attention(Q, K, V)
+            F.scaled_dot_product_attention(case.Q, case.K, case.V)
         torch.cuda.synchronize()
         out["dense_sdpa_fwd_ms"] = (time.perf_counter() - t0) / 3 * 1e3
 

@@ -209,10 +209,14 @@ __global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
     *reinterpret_cast<f32x4 *>(a.dstV + (bh * a.n_l + tok) * 64 + col) = v;
 }
 
-// Highest level the grouped kernel takes; levels above it (none at present) go to the split key-major kernel.
-// Sending a coarsest level of a single key block to the split kernel, to spare the 8 waves a third round for
-// one block, was measured slower (the split kernel re-reads every Q / dO row).
-int dkv_group_top(const Plan &p) { return p.Le; }
+// Highest level the grouped kernel takes; levels above it go to the split key-major kernel.  Only a wide dense
+// coarsest level is left out: every query block would write a partial sum for every one of its key blocks, and
+// summing over all queries is what the split kernel does in registers.  (Sending a coarsest level of a single
+// key block to the split kernel, to spare the 8 waves a third round for one block, was measured slower.)
+int dkv_group_top(const Plan &p) {
+    if (p.Le == p.L && (p.n[p.L] + 15) / 16 > 32) return p.L - 1;
+    return p.Le;
+}
 
 // bytes of the partial slab and of each of the two reduction buffers
 void dkv_group_sizes(const Plan &p, size_t *slab_bytes, size_t *red_bytes) {

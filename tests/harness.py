@@ -124,3 +124,72 @@ def check_close(name, got, ref, tol):
     err, scaled = max_err(got, ref)
     assert scaled <= tol, f"{name}: max-abs err {err:.3e} (scaled {scaled:.3e}) > {tol}"
     return err
+
+
+# ---- large shapes: the oracle checks sampled rows, properties cover every head ----
+def make_inputs_parallel(cfg, seed, threads=8):
+    out = {n: np.empty((cfg["batch"], cfg["heads"], cfg["N"], cfg["d"]), np.float32) for n in ("Q", "K", "V", "dO")}
+    jobs = [(n, b, h) for n in out for b in range(cfg["batch"]) for h in range(cfg["heads"])]
+
+    def one(job):
+        n, b, h = job
+        x = inputs.make_head(cfg["kind"], seed, n, b, h, cfg["N"], cfg["d"])
+        out[n][b, h] = orc.to_bf16(x) if cfg["dtype"] == "bf16" else x
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        list(ex.map(one, jobs))
+    return out
+
+
+def properties_all_heads(cfg, gpu, x):
+    """Checks that need no oracle: valid index lists, gradient sum identities."""
+    plan, g = gpu["plan"], geometry(cfg)
+    for l in range(g.L):
+        I = plan.level_indices(gpu["indices"], l)
+        assert bool((I[..., 1:] > I[..., :-1]).all()) if I.shape[-1] > 1 else True
+        assert int(I.min()) >= 0 and int(I.max()) < g.n(l + 1)
+        if l + 1 < g.L:        # every pick is a child of a pick of the parent row
+            par = plan.level_indices(gpu["indices"], l + 1)                       # [b, h, rows/B, K]
+            parent_of_pick = (I // cfg["B"]).unsqueeze(-1)                         # [b, h, rows, K, 1]
+            rows = I.shape[2]
+            par_rows = par[:, :, torch.arange(rows, device=I.device) // cfg["B"]]  # [b, h, rows, Kp]
+            assert bool((parent_of_pick == par_rows.unsqueeze(-2)).any(-1).all())
+    assert bool(torch.isfinite(gpu["LSE"]).all()) and bool(torch.isfinite(gpu["O"].float()).all())
+    dO, dV = gpu["dO"].float(), gpu["dV"].float()
+    s_ref, s_got = dO.sum(dim=2), dV.sum(dim=2)                                    # [b, h, d]
+    scale = dO.abs().sum(dim=2)
+    assert float(((s_ref - s_got).abs() / scale).max()) < 2e-3, "sum_t dV[t] != sum_q dO[q]"
+    lhs = (gpu["dQ"].float() * gpu["Q"].float()).sum(dim=(2, 3))
+    rhs = (gpu["dK"].float() * gpu["K"].float()).sum(dim=(2, 3))
+    norm = (gpu["dQ"].float().abs() * gpu["Q"].float().abs()).sum(dim=(2, 3))
+    assert float(((lhs - rhs).abs() / norm).max()) < 5e-3, "<dQ,Q> != <dK,K>"
+
+
+def sampled_parity(cfg, gpu, x, heads, n_row_chunks=6, chunk=32, full_backward_head=None):
+    """Pooled levels and indices bit-exact on `heads`; O, LSE, dQ element-wise on sampled runs of query rows;
+    dK, dV element-wise on one whole head if asked (the oracle's full backward must fit the test's time)."""
+    g = geometry(cfg)
+    Le = g.L if cfg.get("Le") is None else cfg["Le"]
+    tol = TOL[cfg["dtype"]]
+    rng = np.random.default_rng(1234)
+    for (b, h) in heads:
+        Qp, Kp, Vp = (orc.pyramid(x[n][b, h], g, cfg["dtype"] == "bf16") for n in ("Q", "K", "V"))
+        ref = {"Qp": Qp, "Kp": Kp, "Vp": Vp, "I": orc.select_all(Qp, Kp, g)}
+        check_pyramid(cfg, gpu, ref, b, h)
+        free_diff, excused = check_indices(cfg, gpu, ref, b, h, x)
+        assert excused == 0 and free_diff == 0
+        idx = orc.cat_indices(ref["I"])
+        Kc, Vc = orc.cat_pyramid(Kp), orc.cat_pyramid(Vp)
+        starts = sorted(set([0, g.N - chunk] + [int(s) for s in rng.integers(0, g.N - chunk, n_row_chunks)]))
+        for s0 in starts:
+            o, lse = orc.attn_fwd(x["Q"][b, h], Kc, Vc, idx, g, Le, rows=(s0, s0 + chunk))
+            dq, _, _ = orc.attn_bwd(x["Q"][b, h], Kc, Vc, idx, x["dO"][b, h], g, Le, rows=(s0, s0 + chunk))
+            sl = slice(s0, s0 + chunk)
+            check_close(f"O{(b, h, s0)}", f32(gpu["O"][b, h, sl]), o[sl], tol["out"])
+            check_close(f"LSE{(b, h, s0)}", f32(gpu["LSE"][b, h, sl]), lse[sl], tol["lse"])
+            check_close(f"dQ{(b, h, s0)}", f32(gpu["dQ"][b, h, sl]), dq[sl], tol["out"])
+        if full_backward_head == (b, h):
+            bw = orc.backward(x["Q"][b, h], Kp, Vp, idx, x["dO"][b, h], g, Le=Le)
+            for name in ("dQ", "dK", "dV"):
+                err = check_close(f"{name}{(b, h)}", f32(gpu[name][b, h]), bw[name], tol["out"])
+                print(f"{cfg['name']} full-head {name} max-abs err {err:.3e}")
