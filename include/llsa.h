@@ -61,9 +61,19 @@ typedef struct {
                            given the very workspace llsa_forward filled                     */
     int32_t kernel_path;/* 0: fastest kernels available for the shape; 1: force the portable
                            scalar kernels (any supported shape, used as a cross-check)      */
+    int32_t single_stream; /* 0: llsa_backward may run independent kernels (the index transpose
+                           beside dQ, the upper levels' dK/dV beside level 1's) on one
+                           auxiliary stream the plan owns, forked from and joined back into
+                           the caller's stream inside the call, so the caller sees plain
+                           stream order; 1: everything goes to the caller's stream            */
 } llsa_desc;
 
-typedef struct llsa_plan_s llsa_plan_t; /* opaque, host-only, immutable after creation */
+/* Opaque and host-side.  The level table and buffer layout never change after creation.  Unless
+   desc.single_stream is set, the first llsa_backward call made outside stream capture creates the
+   plan's auxiliary stream and events on the current device (calls made under capture before that,
+   or on another device, simply stay on the caller's stream); llsa_backward serialises its enqueue
+   sequence per plan, so a plan may be shared by host threads. */
+typedef struct llsa_plan_s llsa_plan_t;
 
 /* Validate a problem and precompute its level table and buffer layout (host only). */
 llsa_status llsa_plan(const llsa_desc *desc, llsa_plan_t **out);

@@ -3,6 +3,7 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -168,7 +169,38 @@ struct StageScope {
 
 using namespace llsa;
 
-struct llsa_plan_s { Plan p; };
+// The plan's auxiliary stream and the events that fork work onto it and join it back.
+struct Aux {
+    std::mutex mu;                       // one llsa_backward enqueue sequence per plan at a time
+    bool tried = false, ok = false;
+    int device = -1;
+    hipStream_t side = nullptr;
+    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // start, lists ready, fork, join
+};
+
+struct llsa_plan_s {
+    Plan p;
+    mutable Aux aux;
+};
+
+// The auxiliary stream if this call may use it: created at the first call that is not under stream capture
+// (nothing may be created while the caller's stream records a graph); later calls reuse it, also under capture.
+static Aux *aux_for_call(const llsa_plan_s *plan, hipStream_t s) {
+    Aux &a = plan->aux;
+    if (plan->p.desc.single_stream || !plan->p.fast) return nullptr;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return nullptr;
+    if (!a.tried) {
+        hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(s, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return nullptr;
+        a.tried = true;
+        a.device = dev;
+        bool ok = hipStreamCreateWithFlags(&a.side, hipStreamNonBlocking) == hipSuccess;
+        for (int i = 0; ok && i < 4; ++i) ok = hipEventCreateWithFlags(&a.ev[i], hipEventDisableTiming) == hipSuccess;
+        a.ok = ok;
+    }
+    return (a.ok && a.device == dev) ? &a : nullptr;
+}
 
 extern "C" {
 
@@ -185,7 +217,13 @@ llsa_status llsa_plan(const llsa_desc *desc, llsa_plan_t **out) {
     return LLSA_OK;
 }
 
-void llsa_plan_destroy(llsa_plan_t *plan) { delete plan; }
+void llsa_plan_destroy(llsa_plan_t *plan) {
+    if (!plan) return;
+    for (hipEvent_t e : plan->aux.ev)
+        if (e) (void)hipEventDestroy(e);
+    if (plan->aux.side) (void)hipStreamDestroy(plan->aux.side);   // returns at once; pending work still completes
+    delete plan;
+}
 
 size_t llsa_plan_workspace_bytes(const llsa_plan_t *plan, int for_backward) {
     if (!plan) return 0;
@@ -291,14 +329,23 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         LLSA_TRY(launch_pool(p, Q, K, V, workspace, false, s));
     }
     float *D = reinterpret_cast<float *>(w + p.D_off);
+    // Independent work goes to the plan's auxiliary stream, unless every stage is being timed one by one.
+    std::lock_guard<std::mutex> lock(plan->aux.mu);
+    Aux *aux = (g_timer.on && g_timer.filter < 0) ? nullptr : aux_for_call(plan, s);
+    hipStream_t side = aux ? aux->side : s;
     if (!p.fast) {                                          // the MFMA dQ kernel produces D itself
         StageScope sc(kBwdPre, call, s);
         LLSA_TRY(launch_bwd_pre(p, O, dO, D, s));
     }
-    {
+    {                                                       // Alg. 2 needs only the indices: beside dQ
         StageScope sc(kTranspose, call, s);
         const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
-        LLSA_TRY(launch_csc(p, top_listed, indices, workspace, s));
+        if (aux) {
+            LLSA_TRY(hipEventRecord(aux->ev[0], s));
+            LLSA_TRY(hipStreamWaitEvent(side, aux->ev[0], 0));
+        }
+        LLSA_TRY(launch_csc(p, top_listed, indices, workspace, side));
+        if (aux) LLSA_TRY(hipEventRecord(aux->ev[1], side));
     }
     LevelTable t = make_level_table(p, K, V, indices, workspace);
     {
@@ -306,12 +353,14 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, O, dO, LSE, D, dQ, s));
         else LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
     }
+    if (aux) LLSA_TRY(hipStreamWaitEvent(s, aux->ev[1], 0));   // the key-major lists are ready from here on
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
     {
         StageScope sc(kDkvCoarse, call, s);
         if (p.group) {                                      // levels above the grouped kernel's range first
             for (int l = p.Le; l > dkv_group_top(p); --l) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
-            LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s));
+            LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, side, aux ? aux->ev[2] : nullptr,
+                                      aux ? aux->ev[3] : nullptr));
         } else for (int l = p.Le; l >= 1; --l) {
             if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
             else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));

@@ -27,7 +27,7 @@ class _Desc(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int32), ("heads", ctypes.c_int32), ("N", ctypes.c_int64), ("d", ctypes.c_int32),
                 ("B", ctypes.c_int32), ("K", ctypes.c_int32), ("L", ctypes.c_int32), ("Le", ctypes.c_int32),
                 ("sm_scale", ctypes.c_float), ("dtype", ctypes.c_int32), ("reweight", ctypes.c_int32),
-                ("bwd_repool", ctypes.c_int32), ("kernel_path", ctypes.c_int32)]
+                ("bwd_repool", ctypes.c_int32), ("kernel_path", ctypes.c_int32), ("single_stream", ctypes.c_int32)]
 
 
 EXPORTS = ["llsa_plan", "llsa_plan_destroy", "llsa_plan_workspace_bytes", "llsa_plan_indices_bytes",
@@ -109,10 +109,10 @@ class Plan:
     """``llsa_plan``: validated problem description, level table and buffer sizes (host only)."""
 
     def __init__(self, batch, heads, N, d, B, K, L, Le=None, sm_scale=0.0, dtype=BF16, reweight=1, bwd_repool=0,
-                 kernel_path=0):
+                 kernel_path=0, single_stream=0):
         lib = load()
         self.desc = _Desc(batch, heads, N, d, B, K, L, L if Le is None else Le, sm_scale, dtype, reweight,
-                          bwd_repool, kernel_path)
+                          bwd_repool, kernel_path, single_stream)
         h = ctypes.c_void_p()
         st = lib.llsa_plan(ctypes.byref(self.desc), ctypes.byref(h))
         self._h = h if st == 0 else None

@@ -153,6 +153,46 @@ def test_backward_repool_matches_reuse():
     assert torch.equal(dQ, a["dQ"]) and torch.equal(dK, a["dK"]) and torch.equal(dV, a["dV"])
 
 
+def test_auxiliary_stream_changes_no_bit():
+    """The backward may fork the index transpose and the upper levels' dK/dV onto the plan's auxiliary stream
+    (default) or keep everything on the caller's stream (single_stream=1): same bits either way, run twice so
+    that the second forked call meets buffers the first one's side work wrote."""
+    cfg = dict(name="streams", batch=2, heads=4, d=64, N=16384, B=16, K=8, L=3, dtype="bf16", kind="smooth")
+    x = H.make_inputs(cfg, 41)
+    ref = H.gpu_forward_backward(cfg, x, plan=H.make_plan(cfg, single_stream=1))
+    plan = H.make_plan(cfg)
+    for _ in range(2):
+        got = H.gpu_forward_backward(cfg, x, plan=plan)
+        for name in ("O", "LSE", "indices", "dQ", "dK", "dV"):
+            assert torch.equal(got[name], ref[name]), name
+
+
+def test_first_backward_under_capture_stays_on_one_stream():
+    """A plan whose very first backward call happens under stream capture must not create its auxiliary stream
+    there; the captured graph still has to reproduce the eager results."""
+    cfg = dict(name="graph_first", batch=1, heads=2, d=64, N=4096, B=16, K=8, L=2, dtype="bf16", kind="smooth")
+    x = H.make_inputs(cfg, 43)
+    ref = H.gpu_forward_backward(cfg, x)
+    plan = H.make_plan(cfg)
+    Q, K, V, dO = ref["Q"], ref["K"], ref["V"], ref["dO"]
+    ws, idx = plan.alloc_workspace(True), plan.alloc_indices()
+    O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
+    LSE = torch.empty_like(ref["LSE"])
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            llsa.forward(plan, Q, K, V, O, LSE, idx, ws)
+            llsa.backward(plan, Q, K, V, O, LSE, idx, dO, ws, dQ, dK, dV)
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(2):
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got in zip(("O", "LSE", "indices", "dQ", "dK", "dV"), (O, LSE, idx, dQ, dK, dV)):
+            assert torch.equal(got, ref[name]), f"replay {rep}: {name}"
+
+
 def test_hip_graph_replays_match_eager():
     """The library never allocates or synchronises, so a forward+backward step can be captured in a HIP graph;
     every replay (with eager work and synchronisations in between) must reproduce the eager results bit for bit."""
