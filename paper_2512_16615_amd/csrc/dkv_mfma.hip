@@ -241,11 +241,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     using S = DkvShape<D>;
     __shared__ __attribute__((aligned(16))) char lds[4][2 * S::TILE + 256];
     __shared__ int len_sh[4];
+    __shared__ __attribute__((aligned(16))) float par_sh[4][2 * D];   // per wave: the parent token's dK | dV
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int i16 = lane & 15, g = lane >> 4;
     const int64_t nkb = a.n_l >> 4;                        // key blocks per head (a multiple of 4)
+    const bool has_par = a.parK != nullptr;
     // The 16 key blocks under one level-1 token draw their queries from one pool (the fine blocks under the
     // level-1 query blocks that listed that token), about 0.5 MB of Q and dO.  Keep the four workgroups of
     // such a group on one XCD (ids congruent modulo 8) so the pool is fetched into one L2 only, and deal
@@ -254,6 +256,25 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     const int64_t kb0 = (int64_t)blockIdx.x * 4;           // this workgroup's four key blocks (same head)
     const int64_t bh = kb0 / nkb;
 
+    // The 16 keys of block j share one parent token (level-1 token j).  Its gradient row is fetched into
+    // registers before the tile loop (so the epilogue does not wait for memory) and handed to the epilogue's
+    // channel layout through the wave's LDS row.
+    float park[D / 64], parv[D / 64];
+    auto par_fetch = [&](int64_t j) {
+#pragma unroll
+        for (int x = 0; x < D / 64; ++x) {
+            park[x] = has_par ? a.parK[(bh * nkb + j) * D + lane + 64 * x] : 0.f;
+            parv[x] = has_par ? a.parV[(bh * nkb + j) * D + lane + 64 * x] : 0.f;
+        }
+    };
+    auto par_publish = [&]() {                              // the wave's own row; its LDS operations stay in order
+#pragma unroll
+        for (int x = 0; x < D / 64; ++x) {
+            par_sh[wave][lane + 64 * x] = park[x];
+            par_sh[wave][D + lane + 64 * x] = parv[x];
+        }
+        __builtin_amdgcn_wave_barrier();
+    };
     // level-0 epilogue: scale dK, add the parent token's share (adjoint of mean pooling), round once
     auto emit = [&](int64_t j, int slot, f32x4 sum) {
         const bool isV = slot >= S::NT;
@@ -262,9 +283,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         if (!isV)
 #pragma unroll
             for (int r = 0; r < 4; ++r) sum[r] *= a.scale;
-        const float *par = isV ? a.parV : a.parK;
-        if (par) {
-            const f32x4 pv = *reinterpret_cast<const f32x4 *>(par + (bh * nkb + j) * D + col);
+        if (has_par) {
+            const f32x4 pv = *reinterpret_cast<const f32x4 *>(&par_sh[wave][(isV ? D : 0) + col]);
 #pragma unroll
             for (int r = 0; r < 4; ++r) sum[r] += pv[r] * 0.0625f;
         }
@@ -283,6 +303,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         if (len <= kSoloMax) {
             bf16x8 kop[S::KS], vop[S::KS];
             f32x4 accK[S::NT], accV[S::NT];
+            par_fetch(j);
 #pragma unroll
             for (int n = 0; n < S::NT; ++n) { accK[n] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[n] = f32x4{0.f, 0.f, 0.f, 0.f}; }
             if (len > 0) {
@@ -290,6 +311,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
                 dkv_tile_loop<D>(a, bh, a.Iq + bh * a.rows * a.Kl_cnt + beg, len, 0, 1, ((int64_t)len + 1) >> 1, kop, vop,
                                  accK, accV, lds[wave], lds[wave] + S::TILE, lane);
             }
+            par_publish();
 #pragma unroll
             for (int n = 0; n < S::NT; ++n) { emit(j, n, accK[n]); emit(j, S::NT + n, accV[n]); }
         }
@@ -305,9 +327,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         f32x4 accK[S::NT], accV[S::NT];
 #pragma unroll
         for (int n = 0; n < S::NT; ++n) { accK[n] = f32x4{0.f, 0.f, 0.f, 0.f}; accV[n] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        par_fetch(j);
         dkv_load_keys<D>(a, bh * a.n_l + j * 16 + i16, lane, kop, vop);
         dkv_tile_loop<D>(a, bh, a.Iq + bh * a.rows * a.Kl_cnt + beg, len, wave, 4, ((int64_t)len + 1) >> 1, kop, vop, accK,
                          accV, lds[wave], lds[wave] + S::TILE, lane);
+        par_publish();
         dkv_reduce_waves<D>(reinterpret_cast<float *>(&lds[0][0]), wave, lane, accK, accV,
                             [&](int slot, f32x4 sum) { emit(j, slot, sum); });
         __syncthreads();                                    // the reduction buffer is the next round's tile space
