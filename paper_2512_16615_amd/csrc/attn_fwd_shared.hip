@@ -114,6 +114,15 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
 
+    // The level-0 lists of this wave's NB query blocks, fetched now so that phase B does not wait for them:
+    // lane (64 / NB) b + j holds the first token of block j of query block b's list (K_0 <= 64 / NB).
+    const int nb0 = t.bseg[1];                                        // K_0 (the list always holds level 0)
+    int tok0 = 0;
+    {
+        const int b = lane / (64 / NB), j = lane % (64 / NB);
+        if (j < nb0) tok0 = t.I[0][(bh * t.rows[0] + blk0 + NB * wave + b) * t.Kl[0] + j] * 16;
+    }
+
     // ------------------------------------------------------------------ phase A: shared coarse levels
     const int c_begin = t.nlev > 1 ? t.bseg[1] : t.bseg[t.nlev];     // first coarse block of the list
     const int nbc = t.bseg[t.nlev] - c_begin;                         // coarse blocks
@@ -181,33 +190,31 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
     }
 
     // ------------------------------------------------------------------ phase B: own level-0 blocks
-    const int nb0 = t.bseg[1];                                        // K_0 (the list always holds level 0)
     char *my = pw[wave];
     const unsigned koff = (unsigned)((i16 * D + g * 8) * 2);
     unsigned voff[VCH];
 #pragma unroll
     for (int u = 0; u < VCH; ++u) voff[u] = (unsigned)((((lane / PARTS + KPU * u) & 15) * D + (lane % PARTS) * 8) * 2);
 
+    // The tiles of the wave's NB query blocks form one stream: the next tile's rows are in flight during the
+    // current tile's math, also across the border between the two blocks (tok0: fetched before phase A).
+    bf16x8 kop[2][KS];
+    u32x4 vreg[VCH];
+    const char *K0 = static_cast<const char *>(t.K[0]), *V0 = static_cast<const char *>(t.V[0]);
+    auto load_tile = [&](int b, int j0) {
+        int64_t off[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j = (j0 + h < nb0) ? j0 + h : j0;               // an absent second half re-reads the first
+            off[h] = (bh * N + __builtin_amdgcn_readlane(tok0, (64 / NB) * b + j)) * (D * 2);
+#pragma unroll
+            for (int s = 0; s < KS; ++s) kop[h][s] = as_bf16x8(gload16(K0 + off[h], koff + 64 * s));
+        }
+#pragma unroll
+        for (int u = 0; u < VCH; ++u) vreg[u] = gload16(V0 + off[(KPU * u) >> 4], voff[u]);
+    };
     auto phase_b = [&](auto bsel) {
         constexpr int b = decltype(bsel)::value;
-        BlockTable tab;
-        tab.fill(t, bh, blk0 + NB * wave + b, 0, 0, lane, D, 1);      // level 0 only (K_0 <= 64 blocks)
-        bf16x8 kop[2][KS];
-        u32x4 vreg[VCH];
-        auto load_tile = [&](int j0) {
-            const char *kp[2], *vp[2];
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int j = (j0 + h < nb0) ? j0 + h : j0;           // an absent second half re-reads the first
-                kp[h] = tab.K(j);
-                vp[h] = tab.V(j);
-#pragma unroll
-                for (int s = 0; s < KS; ++s) kop[h][s] = as_bf16x8(gload16(kp[h], koff + 64 * s));
-            }
-#pragma unroll
-            for (int u = 0; u < VCH; ++u) vreg[u] = gload16(vp[(KPU * u) >> 4], voff[u]);
-        };
-        load_tile(0);
         for (int j0 = 0; j0 < nb0; j0 += 2) {
             __builtin_amdgcn_wave_barrier();                          // one wave's LDS operations stay in order
 #pragma unroll
@@ -222,10 +229,12 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
                 for (int ks = 0; ks < KS; ++ks) s[h] = mfma16(kop[h][ks], qop[b][ks], s[h]);
             }
             const int c1 = (j0 + 1 < nb0) ? 16 : 0;                   // level-0 blocks are always full
-            if (j0 + 2 < nb0) load_tile(j0 + 2);
+            if (j0 + 2 < nb0) load_tile(b, j0 + 2);
+            else if (b + 1 < NB) load_tile(b + 1, 0);
             softmax_pv(bsel, s[0], s[1], 16, c1, 0.f, 0.f, my);
         }
     };
+    load_tile(0, 0);
     phase_b(B0{});
     if constexpr (NB > 1) phase_b(B1{});
 
@@ -249,9 +258,13 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 
 hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                   hipStream_t s) {
-    if (p.d == 64) {                                  // two query blocks per wave (measured faster than one): 16 per workgroup
+    if (p.d == 64 && p.Kl[0] <= 32) {                 // two query blocks per wave (measured faster than one): 16 per workgroup
         const int64_t wgs = (int64_t)p.bh * (p.N / 256);
         attn_fwd_shared_kernel<64, 2><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N,
+                                                                           wgs);
+    } else if (p.d == 64) {                           // K_0 > 32: both level-0 lists would not fit one register
+        const int64_t wgs = (int64_t)p.bh * (p.N / 128);
+        attn_fwd_shared_kernel<64, 1><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N,
                                                                            wgs);
     } else {                                          // d = 128: one query block per wave (registers), 8 per workgroup
         const int64_t wgs = (int64_t)p.bh * (p.N / 128);
