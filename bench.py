@@ -288,7 +288,10 @@ def main():
         case.step()
     torch.cuda.synchronize()
     fwd_flops, bwd_flops = algorithmic_flops(cfg, case.M)
-    stage = "dkv_fine" if args.stage == "auto" else args.stage
+    stage = args.stage
+    if stage == "auto":      # the longest single kernel of the step, from one untimed pass that brackets every stage
+        st = case.stages(2)
+        stage = max(("attn_fwd", "dq", "dkv_fine"), key=lambda k: st.get(k) or 0.0)
 
     # Eager pass: K steps with two HIP events per step around ONE kernel (the roofline kernel).
     llsa.stage_timing_begin(stage, max_calls=args.steps)
