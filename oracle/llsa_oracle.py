@@ -221,6 +221,42 @@ def transpose(I: np.ndarray, T_keys: int):
     return Iq, C
 
 
+# ------------------------------------------------------------------ index reordering (Sec. 5.1)
+
+def nested_order(W: int) -> np.ndarray:
+    """Index reordering for a ``W x W`` pixel grid (W a power of two): ``order[t]`` is the raster index ``y*W + x``
+    of the pixel that becomes token ``t``, such that for every ``i`` the pixels of each aligned patch of size
+    ``2**i x 2**i`` are consecutive tokens.  Written as that definition, recursively: the tokens of a patch are
+    the tokens of its four half-size patches one after the other (upper left, upper right, lower left, lower
+    right; the paper's figure fixes no order among the four, row-major is this build's reading)."""
+    if W < 1 or W & (W - 1):
+        raise ValueError("the pixel grid side must be a power of two")
+
+    def patch(y0: int, x0: int, size: int) -> list[int]:
+        if size == 1:
+            return [y0 * W + x0]
+        h = size // 2
+        return patch(y0, x0, h) + patch(y0, x0 + h, h) + patch(y0 + h, x0, h) + patch(y0 + h, x0 + h, h)
+
+    return np.array(patch(0, 0, W), dtype=np.int64)
+
+
+def reorder(x: np.ndarray, inverse: bool = False) -> np.ndarray:
+    """Applies the index reordering to the token axis of ``x [N, d]`` (N = W*W): raster order -> nested-patch
+    order (``out[t] = x[order[t]]``), or back (``out[order[t]] = x[t]``)."""
+    N = x.shape[0]
+    W = math.isqrt(N)
+    if W * W != N:
+        raise ValueError("index reordering needs a square pixel grid")
+    order = nested_order(W)
+    out = np.empty_like(x)
+    if inverse:
+        out[order] = x
+    else:
+        out[:] = x[order]
+    return out
+
+
 # ------------------------------------------------------------------ whole layer
 
 def forward(Q, K, V, g: Geometry, Le: int | None = None, bf16: bool = False, reweight: int = 1,

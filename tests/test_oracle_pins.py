@@ -397,3 +397,49 @@ def test_transpose_is_exact_and_involutive(oracle):
         for r in Iq[C[key]:C[key + 1]]:
             back[r].append(key)
     assert np.array_equal(np.array(back, np.int32), I)
+
+
+# ------------------------------------------------------------ index reordering (Sec. 5.1)
+
+def test_index_reordering_groups_every_patch_size(oracle):
+    """For every i, each aligned run of 4**i tokens is exactly one aligned 2**i x 2**i patch of pixels."""
+    W = 32
+    order = oracle.nested_order(W)
+    assert np.array_equal(np.sort(order), np.arange(W * W))         # a permutation of the pixels
+    y, x = order // W, order % W
+    for i in range(0, 6):
+        side, run = 2 ** i, 4 ** i
+        for t0 in range(0, W * W, run):
+            ys, xs = y[t0:t0 + run], x[t0:t0 + run]
+            assert ys.min() % side == 0 and xs.min() % side == 0
+            assert ys.max() - ys.min() == side - 1 and xs.max() - xs.min() == side - 1
+            assert len(set(zip(ys.tolist(), xs.tolist()))) == run
+
+
+def test_index_reordering_is_bit_deinterleaving(oracle):
+    """Closed form of the same order: token t's pixel has the even bits of t as x and the odd bits as y."""
+    W = 64
+    order = oracle.nested_order(W)
+    t = np.arange(W * W)
+    xs = sum(((t >> (2 * b)) & 1) << b for b in range(6))
+    ys = sum(((t >> (2 * b + 1)) & 1) << b for b in range(6))
+    assert np.array_equal(order, ys * W + xs)
+    # the 4 x 4 case written out by hand
+    assert oracle.nested_order(4).tolist() == [0, 1, 4, 5, 2, 3, 6, 7, 8, 9, 12, 13, 10, 11, 14, 15]
+
+
+def test_index_reordering_round_trip_and_pooling_meaning(oracle):
+    rng = np.random.default_rng(23)
+    W, d = 16, 8
+    x = rng.standard_normal((W * W, d)).astype(np.float32)
+    r = oracle.reorder(x)
+    assert np.array_equal(oracle.reorder(r, inverse=True), x)
+    assert not np.array_equal(r, x)
+    # pooling 16 consecutive reordered tokens = the mean over a 4 x 4 pixel patch of the raster image
+    pooled = oracle.pool(r, 16, False)
+    img = x.reshape(W, W, d).astype(np.float64)
+    for py in range(W // 4):
+        for px in range(W // 4):
+            want = img[4 * py:4 * py + 4, 4 * px:4 * px + 4].reshape(16, d).mean(axis=0)
+            t = int(np.nonzero(oracle.nested_order(W) == (4 * py) * W + 4 * px)[0][0]) // 16
+            assert np.allclose(pooled[t], want, rtol=0, atol=1e-6)
