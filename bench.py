@@ -245,6 +245,9 @@ def main():
     ap.add_argument("--dense-compare", action="store_true", help="also time dense bf16 SDPA (forward) on this GPU")
     ap.add_argument("--force-generic", action="store_true", help="run the portable scalar kernels")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP-graph replays of the step")
+    ap.add_argument("--order", default="raster", choices=["raster", "nested"],
+                    help="token order of the pixel grid: raster (BASELINE's) or the paper's nested-patch index reordering, "
+                         "applied once with llsa_reorder before the timed region")
     ap.add_argument("--single-stream", action="store_true",
                     help="keep the backward on the caller's stream (no fork onto the plan's auxiliary stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -283,6 +286,12 @@ def main():
     dev, x = device_inputs(cfg, inputs.config_seed(args.config), keep_host=not args.no_cpu)
     print(f"[bench] inputs ready in {time.time() - t0:.1f} s", file=sys.stderr, flush=True)
 
+    if args.order == "nested":                               # once per model in the paper: outside the timed region
+        from oracle import llsa_oracle as orc
+        dev = {n: llsa.reorder(v) for n, v in dev.items()}
+        if x is not None:
+            x = {n: np.stack([np.stack([orc.reorder(v[b, h]) for h in range(v.shape[1])]) for b in range(v.shape[0])])
+                 for n, v in x.items()}
     case = Case(cfg, dev, Le=args.Le, force_generic=args.force_generic, single_stream=args.single_stream)
     for _ in range(args.warmup):
         case.step()
@@ -341,7 +350,7 @@ def main():
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"BASELINE configs[{args.config}] {cfg['name']}: batch {cfg['batch']}, heads {cfg['heads']}, "
                                f"d {cfg['d']}, N {cfg['N']}, B {cfg['B']}, K {cfg['K']}, L {cfg['L']}, Le {case.Le}, "
-                               f"{cfg['kind']} inputs, forward+backward",
+                               f"{cfg['kind']} inputs in {args.order} token order, forward+backward",
                    "gathered_tokens_per_query": case.M, "kernels": "generic" if args.force_generic else "default",
                    "launch": mode, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
                    "streams": "caller's stream only" if args.single_stream else "caller's stream + one auxiliary stream inside llsa_backward"},

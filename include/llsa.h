@@ -146,6 +146,19 @@ llsa_status llsa_attention(const llsa_plan_t *plan, const void *Q, const void *K
 /* Alg. 2 for every level: builds the key-major lists inside the backward workspace. */
 llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices, void *workspace, void *hip_stream);
 
+/*
+ * Index reordering for 2-D token grids (Sec. 5.1, "Index Reordering"), applied once per model, outside
+ * llsa_forward / llsa_backward: N = W * W tokens of a W x W pixel grid in raster order, W a power of two.
+ * inverse = 0: out[bh][t] = in[bh][y * W + x], where x / y are the even / odd bits of t, so that for every i
+ * each aligned run of 4^i tokens is one aligned 2^i x 2^i patch of pixels (nested patches; the four quarters
+ * of a patch in row-major order).  inverse = 1 undoes it: out[bh][y * W + x] = in[bh][t].
+ *   in, out : device, [batch_heads, N, d] of `dtype`, contiguous, caller-owned, not overlapping
+ * Errors: LLSA_ERR_NULL; LLSA_ERR_UNSUPPORTED for an unknown dtype; LLSA_ERR_BAD_SHAPE if N is not a power
+ * of four, a row is not a multiple of 16 bytes, or the buffers overlap.  Nothing is enqueued on error.
+ */
+llsa_status llsa_reorder(int64_t batch_heads, int64_t N, int32_t d, int32_t dtype, int32_t inverse, const void *in,
+                         void *out, void *hip_stream);
+
 /* ---- per-stage timing for benchmarks (Sec. 5.4 reports kernel-level speed; this is how it is read here) ----
  * Stages: 0 pool, 1 select, 2 attention forward, 3 D = rowsum(dO*O), 4 index transpose, 5 dQ,
  * 6 dK/dV of the coarse levels, 7 un-pooling, 8 dK/dV of level 0.

@@ -598,4 +598,33 @@ hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s) {
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------- index reordering (Sec. 5.1)
+// Tokens of a W x W pixel grid in nested-patch order: token t is the pixel whose x / y are the even / odd bits
+// of t, so every aligned run of 4^i tokens is one aligned 2^i x 2^i patch.  One thread per 16-byte chunk of a
+// row; forward: out[t] = in[y W + x], inverse: out[y W + x] = in[t].
+__global__ void __launch_bounds__(256) reorder_kernel(const uint4 *in, uint4 *out, int64_t N, int cpr, int bits,
+                                                       int inverse, int64_t total) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int64_t row = idx / cpr, bh = row / N, t = row % N;
+    const int c = (int)(idx % cpr);
+    int64_t x = 0, y = 0;
+    for (int b = 0; b < bits; ++b) {
+        x |= ((t >> (2 * b)) & 1) << b;
+        y |= ((t >> (2 * b + 1)) & 1) << b;
+    }
+    const int64_t r = (y << bits) + x;
+    const int64_t src = inverse ? t : r, dst = inverse ? r : t;
+    out[(bh * N + dst) * cpr + c] = in[(bh * N + src) * cpr + c];
+}
+
+hipError_t launch_reorder(int64_t bh, int64_t N, int row_bytes, int bits, int inverse, const void *in, void *out,
+                          hipStream_t s) {
+    const int cpr = row_bytes / 16;
+    const int64_t total = bh * N * cpr;
+    reorder_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint4 *)in, (uint4 *)out, N, cpr, bits, inverse,
+                                                                   total);
+    return hipGetLastError();
+}
+
 }  // namespace llsa

@@ -377,6 +377,22 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     return LLSA_OK;
 }
 
+llsa_status llsa_reorder(int64_t batch_heads, int64_t N, int32_t d, int32_t dtype, int32_t inverse, const void *in,
+                         void *out, void *hip_stream) {
+    if (!in || !out) return LLSA_ERR_NULL;
+    if (dtype != LLSA_F32 && dtype != LLSA_BF16) return LLSA_ERR_UNSUPPORTED;
+    if (batch_heads < 1 || N < 1 || d < 1 || N > ((int64_t)1 << 30) || batch_heads > (1 << 20)) return LLSA_ERR_BAD_SHAPE;
+    int bits = 0;
+    while (((int64_t)1 << (2 * bits)) < N) ++bits;
+    const int64_t row_bytes = (int64_t)d * (dtype == LLSA_F32 ? 4 : 2);
+    if (((int64_t)1 << (2 * bits)) != N || row_bytes % 16 != 0 || row_bytes > (1 << 16)) return LLSA_ERR_BAD_SHAPE;
+    const char *a = static_cast<const char *>(in), *b = static_cast<const char *>(out);
+    const int64_t bytes = batch_heads * N * row_bytes;
+    if (a < b + bytes && b < a + bytes) return LLSA_ERR_BAD_SHAPE;      // the copy is not in place
+    LLSA_TRY(launch_reorder(batch_heads, N, (int)row_bytes, bits, inverse ? 1 : 0, in, out, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
 int32_t llsa_stage_count(void) { return kStages; }
 
 const char *llsa_stage_name(int32_t stage) { return (stage >= 0 && stage < kStages) ? kStageNames[stage] : ""; }

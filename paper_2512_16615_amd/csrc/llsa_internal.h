@@ -66,6 +66,9 @@ hipError_t launch_dq_generic(const Plan &p, const LevelTable &t, const void *Q, 
 hipError_t launch_dkv_generic(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO,
                               const float *LSE, const float *D, void *ws, void *dK, void *dV, hipStream_t s);
 hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
+// nested-patch token order of a 2^bits x 2^bits grid (or back); rows of row_bytes (a multiple of 16) bytes
+hipError_t launch_reorder(int64_t bh, int64_t N, int row_bytes, int bits, int inverse, const void *in, void *out,
+                          hipStream_t s);
 
 // ---- fast selection (bf16, B = 16, <= 128 candidates, K <= 16) ----
 bool select_fast_ok(const Plan &p, int l);

@@ -32,7 +32,7 @@ class _Desc(ctypes.Structure):
 
 EXPORTS = ["llsa_plan", "llsa_plan_destroy", "llsa_plan_workspace_bytes", "llsa_plan_indices_bytes",
            "llsa_plan_level_info", "llsa_plan_pyramid_info", "llsa_plan_csc_info", "llsa_forward", "llsa_backward",
-           "llsa_pool", "llsa_select_level", "llsa_attention", "llsa_index_transpose", "llsa_status_string",
+           "llsa_pool", "llsa_select_level", "llsa_attention", "llsa_index_transpose", "llsa_reorder", "llsa_status_string",
            "llsa_stage_count", "llsa_stage_name", "llsa_stage_timing_begin", "llsa_stage_timing_end"]
 
 
@@ -71,6 +71,8 @@ def load():
     lib.llsa_attention.restype = ctypes.c_int
     lib.llsa_index_transpose.argtypes = [vp] * 4
     lib.llsa_index_transpose.restype = ctypes.c_int
+    lib.llsa_reorder.argtypes = [i64, i64, i32, i32, i32, vp, vp, vp]
+    lib.llsa_reorder.restype = ctypes.c_int
     lib.llsa_stage_count.argtypes = []
     lib.llsa_stage_count.restype = i32
     lib.llsa_stage_name.argtypes = [i32]
@@ -240,6 +242,19 @@ def attention(p: Plan, Q, K, V, indices, workspace, O=None, LSE=None):
 def index_transpose(p: Plan, indices, workspace):
     """``llsa_index_transpose``: key-major lists of every level into a backward workspace."""
     _check(load().llsa_index_transpose(p._h, _ptr(indices), _ptr(workspace), _stream()), "llsa_index_transpose")
+
+
+def reorder(x: torch.Tensor, inverse: bool = False, out: torch.Tensor | None = None) -> torch.Tensor:
+    """``llsa_reorder``: tokens of ``x [..., N, d]`` (N = W*W, raster order) into nested-patch order, or back."""
+    if not x.is_contiguous():
+        raise LlsaError("llsa_reorder needs a contiguous tensor")
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(x.dtype)
+    if dtype is None:
+        raise LlsaError("llsa_reorder: fp32 or bf16 only")
+    N, d = x.shape[-2], x.shape[-1]
+    out = torch.empty_like(x) if out is None else out
+    _check(load().llsa_reorder(x.numel() // (N * d), N, d, dtype, int(inverse), _ptr(x), _ptr(out), _stream()), "llsa_reorder")
+    return out
 
 
 def stage_names() -> list[str]:

@@ -57,3 +57,49 @@ def test_block_size_64_portable_kernels():
     """B = 64 (the larger block of the paper's efficiency comparison): N = 16384 -> 256 -> 4 tokens, L = 2."""
     cfg = dict(BASE, name="n16384_B64", N=16384, heads=2, B=64, K=4, L=2)
     _run(cfg, 0x115A2050, heads=[(0, 1)], n_row_chunks=3, full_backward_head=(0, 1))
+
+
+# ---- index reordering (Sec. 5.1): the tokens of a pixel grid in nested-patch order
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_index_reordering_matches_oracle(dtype):
+    import numpy as np
+    import torch
+    from oracle import llsa_oracle as orc
+    from paper_2512_16615_amd import llsa
+    rng = np.random.default_rng(7)
+    bh, N, d = 3, 4096, 64
+    x = rng.standard_normal((bh, N, d)).astype(np.float32)
+    if dtype == "bf16":
+        x = orc.to_bf16(x)
+    dev = torch.from_numpy(x).cuda()
+    dev = dev.to(torch.bfloat16) if dtype == "bf16" else dev
+    fwd = llsa.reorder(dev)
+    back = llsa.reorder(fwd, inverse=True)
+    torch.cuda.synchronize()
+    for h in range(bh):
+        assert np.array_equal(fwd[h].float().cpu().numpy(), orc.reorder(x[h])), "forward order differs from the oracle"
+    assert torch.equal(back, dev)
+    with pytest.raises(llsa.LlsaError):                      # 2048 tokens are not a square power-of-two grid
+        llsa.reorder(dev[:, :2048].contiguous())
+    with pytest.raises(llsa.LlsaError):                      # in place is refused
+        llsa.reorder(dev, out=dev)
+
+
+def test_layer_on_reordered_tokens():
+    """The layer on nested-patch token order (what the paper's DiT feeds it): inputs reordered on the GPU equal the
+    oracle's reordering, and forward + backward on them meet the usual bars (16 consecutive tokens = a 4 x 4 patch)."""
+    import numpy as np
+    import torch
+    from oracle import llsa_oracle as orc
+    from paper_2512_16615_amd import llsa
+    cfg = dict(BASE, name="n16384_nested", N=16384, heads=2, L=3)
+    raster = H.make_inputs_parallel(cfg, 0x115A2060)
+    nested = {n: np.stack([np.stack([orc.reorder(v[b, h]) for h in range(cfg["heads"])]) for b in range(cfg["batch"])])
+              for n, v in raster.items()}
+    for n in raster:
+        got = llsa.reorder(H.to_dev(raster[n], cfg))
+        assert torch.equal(got, H.to_dev(nested[n], cfg)), n
+    gpu = H.gpu_forward_backward(cfg, nested)
+    H.properties_all_heads(cfg, gpu, nested)
+    H.sampled_parity(cfg, gpu, nested, heads=[(0, 1)], n_row_chunks=3, full_backward_head=(0, 1))
