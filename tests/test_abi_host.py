@@ -79,3 +79,27 @@ def test_null_pointers_are_refused_before_any_launch(llsa):
     assert lib.llsa_backward(p._h, *([None] * 12)) == 1
     assert lib.llsa_plan(None, None) == 1
     assert lib.llsa_status_string(0) == b"ok"
+
+
+def test_desc_layout_matches_the_header(llsa):
+    """The binding's struct must list the header's fields in the header's order (same C layout)."""
+    text = open(os.path.join(ROOT, "include", "llsa.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} llsa_desc;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    names = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if decl:
+            names += [n.strip() for n in decl.split(None, 1)[1].split(",")]
+    assert names == [f[0] for f in llsa._Desc._fields_]
+
+
+def test_reorder_validates_on_the_host(llsa):
+    """llsa_reorder refuses bad calls before anything is enqueued (no GPU needed to see that)."""
+    lib = llsa.load()
+    a, b = ctypes.c_void_p(4096), ctypes.c_void_p(1 << 30)       # never dereferenced: every call below is refused
+    assert lib.llsa_reorder(1, 4096, 64, llsa.BF16, 0, None, b, None) == 1
+    assert lib.llsa_reorder(1, 2048, 64, llsa.BF16, 0, a, b, None) == 2     # not a power of four
+    assert lib.llsa_reorder(1, 4096, 4, llsa.BF16, 0, a, b, None) == 2      # 8-byte rows
+    assert lib.llsa_reorder(1, 4096, 64, 9, 0, a, b, None) == 3             # unknown dtype
+    assert lib.llsa_reorder(1, 4096, 64, llsa.BF16, 0, a, ctypes.c_void_p(4096 + 128), None) == 2   # overlap
