@@ -338,12 +338,12 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         LLSA_TRY(launch_bwd_pre(p, O, dO, D, s));
     }
     {                                                       // Alg. 2 needs only the indices: beside dQ
-        StageScope sc(kTranspose, call, s);
         const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
         if (aux) {
             LLSA_TRY(hipEventRecord(aux->ev[0], s));
             LLSA_TRY(hipStreamWaitEvent(side, aux->ev[0], 0));
         }
+        StageScope sc(kTranspose, call, side);              // bracketed on the stream it runs on
         LLSA_TRY(launch_csc(p, top_listed, indices, workspace, side));
         if (aux) LLSA_TRY(hipEventRecord(aux->ev[1], side));
     }

@@ -77,6 +77,12 @@ def test_config1_n4096_bf16_all_heads():
     dict(name="ragged_top_d128", batch=2, heads=1, d=128, N=16 * 16 * 3, B=16, K=2, L=2, dtype="bf16", kind="gaussian"),
     # larger K sweep value
     dict(name="K16", batch=1, heads=2, d=64, N=4096, B=16, K=16, L=2, dtype="bf16", kind="smooth"),
+    # grouped coarse dK/dV with an odd number of level-1 query blocks (5) and a ragged dense level of 5 tokens
+    dict(name="five_groups", batch=1, heads=3, d=64, N=1280, B=16, K=8, L=2, dtype="bf16", kind="gaussian"),
+    # three level-2 query blocks (48 level-1 blocks), dense top of 3 tokens, tiny K; and K = 3 lists at every level
+    dict(name="three_supergroups", batch=1, heads=2, d=64, N=12288, B=16, K=3, L=3, dtype="bf16", kind="gaussian"),
+    # four coarse levels with a one-token top: 13 listed blocks at levels 2 and 3 (two per wave, some waves one)
+    dict(name="K12_L4", batch=1, heads=1, d=64, N=65536, B=16, K=12, L=4, Le=4, dtype="bf16", kind="gaussian"),
 ])
 def test_edge_shapes(cfg):
     _full_parity(cfg, 0x5EED0 + len(cfg["name"]))

@@ -53,6 +53,13 @@ def test_n1048576_d64_L4():
     _run(cfg, 0x115A2040, heads=[(0, 0)], n_row_chunks=2)
 
 
+@pytest.mark.timeout(600)
+def test_n1048576_K16_two_upper_launches():
+    """K = 16 at L = 4: 32 listed blocks at levels 2 and 3, which the upper-level dK/dV kernel takes in two launches."""
+    cfg = dict(BASE, name="n1048576_K16", N=1048576, heads=1, L=4, K=16)
+    _run(cfg, 0x115A2070, heads=[(0, 0)], n_row_chunks=2)
+
+
 def test_block_size_64_portable_kernels():
     """B = 64 (the larger block of the paper's efficiency comparison): N = 16384 -> 256 -> 4 tokens, L = 2."""
     cfg = dict(BASE, name="n16384_B64", N=16384, heads=2, B=64, K=4, L=2)
