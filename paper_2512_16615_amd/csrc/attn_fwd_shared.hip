@@ -37,8 +37,13 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
     constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, PARTS = D / 8, TILE = 32 * STRIDE;
     constexpr int RND = (2 * 32 * PARTS) / 512;         // staging rounds of the workgroup per shared tile (K and V)
     constexpr int VCH = D / 16, KPU = 64 / PARTS;       // private V staging of one wave (phase B)
-    __shared__ __attribute__((aligned(16))) char sh[2][2][TILE];      // [buffer][K | V]
-    __shared__ __attribute__((aligned(16))) char pw[8][TILE];         // per-wave V tile (phase B)
+    // Phase B: per wave a K tile (row-wise reads: rows 32 bytes apart in the banks) and a V tile (transposed reads only:
+    // 16 bytes of padding do).  Phase A's two double-buffered [K | V] tiles live in the first 4 TILE bytes of the same
+    // memory; a workgroup barrier separates the phases.
+    constexpr int VSTRIDE = D * 2 + 16, VTILE = 32 * VSTRIDE;
+    __shared__ __attribute__((aligned(16))) char lds[8 * (TILE + VTILE)];
+    static_assert(4 * TILE <= 8 * (TILE + VTILE), "phase A's buffers must fit");
+    auto sh = [&](int buf, int which) { return lds + (buf * 2 + which) * TILE; };
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -64,8 +69,9 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 
     // softmax update of query block b for one tile (s0 / s1: S^T of the two halves) and O^T += V^T P^T
     // with the V tile at `vt` (row-major, STRIDE bytes per key row)
-    auto softmax_pv = [&](auto bsel, f32x4 s0, f32x4 s1, int c0, int c1, float b0, float b1, const char *vt) {
+    auto softmax_pv = [&](auto bsel, f32x4 s0, f32x4 s1, int c0, int c1, float b0, float b1, const char *vt, auto vstride) {
         constexpr int b = decltype(bsel)::value;
+        constexpr int VS = decltype(vstride)::value;                  // bytes between the V tile's key rows
         f32x4 s[2] = {s0, s1};
         const float b2[2] = {b0, b1};
         const int c[2] = {c0, c1};
@@ -106,11 +112,13 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
                 lsum[b] += s[h][r];
             }
         const bf16x8 pop = pack8(s[0], s[1]);
-        const char *base = vt + (4 * g + (i16 >> 2)) * STRIDE + (i16 & 3) * 8;
+        const char *base = vt + (4 * g + (i16 >> 2)) * VS + (i16 & 3) * 8;
 #pragma unroll
         for (int n = 0; n < NT; ++n)
-            acc[b][n] = mfma16(lds_tr_pair(base + n * 32, base + 16 * STRIDE + n * 32), pop, acc[b][n]);
+            acc[b][n] = mfma16(lds_tr_pair(base + n * 32, base + 16 * VS + n * 32), pop, acc[b][n]);
     };
+    using StrideA = std::integral_constant<int, STRIDE>;
+    using StrideB = std::integral_constant<int, VSTRIDE>;
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
 
@@ -148,7 +156,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
             for (int r = 0; r < RND; ++r) {
                 const int cc = tid + 512 * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
-                *reinterpret_cast<u32x4 *>(sh[buf][which] + (c / PARTS) * STRIDE + (c % PARTS) * 16) = sreg[r];
+                *reinterpret_cast<u32x4 *>(sh(buf, which) + (c / PARTS) * STRIDE + (c % PARTS) * 16) = sreg[r];
             }
         };
         const int ntile = (nbc + 1) >> 1;
@@ -168,7 +176,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
             }
             __syncthreads();                                          // tile u visible; buffer buf^1 free again
             if (u + 1 < ntile) load_shared(u + 1);
-            const char *kt = sh[buf][0], *vt = sh[buf][1];
+            const char *kt = sh(buf, 0), *vt = sh(buf, 1);
             bf16x8 kop[2][KS];
 #pragma unroll
             for (int h = 0; h < 2; ++h)
@@ -184,22 +192,24 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) s[b][h] = mfma16(kop[h][ks], qop[b][ks], s[b][h]);
                 }
-            softmax_pv(B0{}, s[0][0], s[0][1], cnt[0], cnt[1], bias2[0], bias2[1], vt);
-            if constexpr (NB > 1) softmax_pv(B1{}, s[NB - 1][0], s[NB - 1][1], cnt[0], cnt[1], bias2[0], bias2[1], vt);
+            softmax_pv(B0{}, s[0][0], s[0][1], cnt[0], cnt[1], bias2[0], bias2[1], vt, StrideA{});
+            if constexpr (NB > 1) softmax_pv(B1{}, s[NB - 1][0], s[NB - 1][1], cnt[0], cnt[1], bias2[0], bias2[1], vt, StrideA{});
         }
     }
 
     // ------------------------------------------------------------------ phase B: own level-0 blocks
-    char *my = pw[wave];
-    const unsigned koff = (unsigned)((i16 * D + g * 8) * 2);
+    // K and V rows are fetched with 8 consecutive lanes per 128-byte row (whole cache lines per instruction: loading
+    // the MFMA operand layout straight from memory, 16 rows x half a line per instruction, caps the gather rate at a
+    // third of what the L2 delivers) and reach the operand layouts through the wave's own LDS tiles.
+    __syncthreads();                                                  // phase A's buffers are free
+    char *my_k = lds + wave * (TILE + VTILE), *my_v = my_k + TILE;
     unsigned voff[VCH];
 #pragma unroll
     for (int u = 0; u < VCH; ++u) voff[u] = (unsigned)((((lane / PARTS + KPU * u) & 15) * D + (lane % PARTS) * 8) * 2);
 
     // The tiles of the wave's NB query blocks form one stream: the next tile's rows are in flight during the
     // current tile's math, also across the border between the two blocks (tok0: fetched before phase A).
-    bf16x8 kop[2][KS];
-    u32x4 vreg[VCH];
+    u32x4 kreg[VCH], vreg[VCH];
     const char *K0 = static_cast<const char *>(t.K[0]), *V0 = static_cast<const char *>(t.V[0]);
     auto load_tile = [&](int b, int j0) {
         int64_t off[2];
@@ -207,31 +217,35 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
         for (int h = 0; h < 2; ++h) {
             const int j = (j0 + h < nb0) ? j0 + h : j0;               // an absent second half re-reads the first
             off[h] = (bh * N + __builtin_amdgcn_readlane(tok0, (64 / NB) * b + j)) * (D * 2);
-#pragma unroll
-            for (int s = 0; s < KS; ++s) kop[h][s] = as_bf16x8(gload16(K0 + off[h], koff + 64 * s));
         }
 #pragma unroll
-        for (int u = 0; u < VCH; ++u) vreg[u] = gload16(V0 + off[(KPU * u) >> 4], voff[u]);
+        for (int u = 0; u < VCH; ++u) {
+            kreg[u] = gload16(K0 + off[(KPU * u) >> 4], voff[u]);
+            vreg[u] = gload16(V0 + off[(KPU * u) >> 4], voff[u]);
+        }
     };
     auto phase_b = [&](auto bsel) {
         constexpr int b = decltype(bsel)::value;
         for (int j0 = 0; j0 < nb0; j0 += 2) {
             __builtin_amdgcn_wave_barrier();                          // one wave's LDS operations stay in order
 #pragma unroll
-            for (int u = 0; u < VCH; ++u)
-                *reinterpret_cast<u32x4 *>(my + (lane / PARTS + KPU * u) * STRIDE + (lane % PARTS) * 16) = vreg[u];
+            for (int u = 0; u < VCH; ++u) {
+                *reinterpret_cast<u32x4 *>(my_k + (lane / PARTS + KPU * u) * STRIDE + (lane % PARTS) * 16) = kreg[u];
+                *reinterpret_cast<u32x4 *>(my_v + (lane / PARTS + KPU * u) * VSTRIDE + (lane % PARTS) * 16) = vreg[u];
+            }
             __builtin_amdgcn_wave_barrier();
+            if (j0 + 2 < nb0) load_tile(b, j0 + 2);                   // the registers are free again: next tile's rows
+            else if (b + 1 < NB) load_tile(b + 1, 0);                 // fly during all of this tile's math
             f32x4 s[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int ks = 0; ks < KS; ++ks) s[h] = mfma16(kop[h][ks], qop[b][ks], s[h]);
+                for (int ks = 0; ks < KS; ++ks)
+                    s[h] = mfma16(*reinterpret_cast<const bf16x8 *>(my_k + (h * 16 + i16) * STRIDE + g * 16 + ks * 64), qop[b][ks], s[h]);
             }
             const int c1 = (j0 + 1 < nb0) ? 16 : 0;                   // level-0 blocks are always full
-            if (j0 + 2 < nb0) load_tile(b, j0 + 2);
-            else if (b + 1 < NB) load_tile(b + 1, 0);
-            softmax_pv(bsel, s[0], s[1], 16, c1, 0.f, 0.f, my);
+            softmax_pv(bsel, s[0], s[1], 16, c1, 0.f, 0.f, my_v, StrideB{});
         }
     };
     load_tile(0, 0);

@@ -32,8 +32,13 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
                  uint16_t *__restrict__ dQ, int64_t N, int64_t total_wgs) {
     constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, PARTS = D / 8, TILE = 32 * STRIDE;
     constexpr int RND = (2 * 32 * PARTS) / 512, VCH = D / 16, KPU = 64 / PARTS;
-    __shared__ __attribute__((aligned(16))) char sh[2][2][TILE];      // [buffer][K | V]
-    __shared__ __attribute__((aligned(16))) char pw[8][TILE];         // per-wave K tile (phase B)
+    // Phase B: per wave a K tile (row-wise and transposed reads) and a V tile (row-wise reads only; 16 bytes of
+    // padding keep it smaller).  Phase A's two double-buffered [K | V] tiles live in the first 4 TILE bytes of the
+    // same memory; a workgroup barrier separates the phases.
+    constexpr int VSTRIDE = D * 2 + 16, VTILE = 32 * VSTRIDE;
+    __shared__ __attribute__((aligned(16))) char lds[8 * (TILE + VTILE)];
+    static_assert(4 * TILE <= 8 * (TILE + VTILE), "phase A's buffers must fit");
+    auto sh = [&](int buf, int which) { return lds + (buf * 2 + which) * TILE; };
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -125,7 +130,7 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
 #pragma unroll
             for (int r = 0; r < RND; ++r) {
                 const int cc = tid + 512 * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
-                *reinterpret_cast<u32x4 *>(sh[buf][which] + (c / PARTS) * STRIDE + (c % PARTS) * 16) = sreg[r];
+                *reinterpret_cast<u32x4 *>(sh(buf, which) + (c / PARTS) * STRIDE + (c % PARTS) * 16) = sreg[r];
             }
         };
         const int ntile = (nbc + 1) >> 1;
@@ -144,7 +149,7 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
             }
             __syncthreads();
             if (u + 1 < ntile) load_shared(u + 1);
-            const char *kt = sh[buf][0], *vt = sh[buf][1];
+            const char *kt = sh(buf, 0), *vt = sh(buf, 1);
             // one query block at a time keeps the live score registers low (the row-wise operands are
             // re-read from LDS for the second block)
             auto scores = [&](auto bsel) {
@@ -169,9 +174,12 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
     }
 
     // ------------------------------------------------------------------ phase B: own level-0 blocks
+    // K and V rows are fetched with 8 consecutive lanes per 128-byte row (whole cache lines per instruction: loading
+    // the MFMA operand layout straight from memory, 16 rows x half a line per instruction, caps the gather rate at a
+    // third of what the L2 delivers) and reach the operand layouts through the wave's own LDS tiles.
+    __syncthreads();                                                  // phase A's buffers are free
     const int nb0 = t.bseg[1];
-    char *my = pw[wave];
-    const unsigned koff = (unsigned)((i16 * D + g * 8) * 2);
+    char *my = lds + wave * (TILE + VTILE), *my_v = my + TILE;
     unsigned voff[VCH];
 #pragma unroll
     for (int u = 0; u < VCH; ++u) voff[u] = (unsigned)((((lane / PARTS + KPU * u) & 15) * D + (lane % PARTS) * 8) * 2);
@@ -180,8 +188,7 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
         constexpr int b = decltype(bsel)::value;
         BlockTable tab;
         tab.fill(t, bh, blk0 + NB * wave + b, 0, 0, lane, D, 1);      // level 0 only
-        bf16x8 vop[2][KS];
-        u32x4 kreg[VCH];
+        u32x4 kreg[VCH], vreg[VCH];
         auto load_tile = [&](int j0) {
             const char *kp[2], *vp[2];
 #pragma unroll
@@ -189,33 +196,36 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
                 const int j = (j0 + h < nb0) ? j0 + h : j0;
                 kp[h] = tab.K(j);
                 vp[h] = tab.V(j);
-#pragma unroll
-                for (int s = 0; s < KS; ++s) vop[h][s] = to_bf16x8(gload16b(vp[h], koff + 64 * s));
             }
 #pragma unroll
-            for (int u = 0; u < VCH; ++u) kreg[u] = gload16b(kp[(KPU * u) >> 4], voff[u]);
+            for (int u = 0; u < VCH; ++u) {
+                kreg[u] = gload16b(kp[(KPU * u) >> 4], voff[u]);
+                vreg[u] = gload16b(vp[(KPU * u) >> 4], voff[u]);
+            }
         };
         load_tile(0);
         for (int j0 = 0; j0 < nb0; j0 += 2) {
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
-            for (int u = 0; u < VCH; ++u)
+            for (int u = 0; u < VCH; ++u) {
                 *reinterpret_cast<u32x4 *>(my + (lane / PARTS + KPU * u) * STRIDE + (lane % PARTS) * 16) = kreg[u];
+                *reinterpret_cast<u32x4 *>(my_v + (lane / PARTS + KPU * u) * VSTRIDE + (lane % PARTS) * 16) = vreg[u];
+            }
             __builtin_amdgcn_wave_barrier();
+            if (j0 + 2 < nb0) load_tile(j0 + 2);                      // the registers are free again
             f32x4 s[2], dp[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
                 s[h] = f32x4{0.f, 0.f, 0.f, 0.f};
                 dp[h] = f32x4{0.f, 0.f, 0.f, 0.f};
-                const char *krow = my + (h * 16 + i16) * STRIDE + g * 16;
+                const char *krow = my + (h * 16 + i16) * STRIDE + g * 16, *vrow = my_v + (h * 16 + i16) * VSTRIDE + g * 16;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
                     s[h] = mfma16(*reinterpret_cast<const bf16x8 *>(krow + ks * 64), qop[b][ks], s[h]);
-                    dp[h] = mfma16(vop[h][ks], gop[b][ks], dp[h]);
+                    dp[h] = mfma16(*reinterpret_cast<const bf16x8 *>(vrow + ks * 64), gop[b][ks], dp[h]);
                 }
             }
             const int c1 = (j0 + 1 < nb0) ? 16 : 0;
-            if (j0 + 2 < nb0) load_tile(j0 + 2);
             ds_dq(bsel, s[0], s[1], dp[0], dp[1], 16, c1, 0.f, 0.f, my);
         }
     };
