@@ -82,22 +82,36 @@ template <class T> __device__ __forceinline__ float dot_row(const T *row, const 
 // selection below is decided on these values, so they must not depend on the launch shape.
 struct PoolArgs { const void *in[3]; void *out[3]; };
 
-template <class T>
-__global__ void __launch_bounds__(256) pool_kernel(PoolArgs a, int64_t n_out_total, int d, int B) {
+// BC: block size known at compile time (the row loop is unrolled, so all B loads of a thread are in flight at once),
+// or 0 to take it from the argument.  Same order of additions either way.
+template <class T, int BC>
+__global__ void __launch_bounds__(256) pool_kernel(PoolArgs a, int64_t n_out_total, int d, int B_arg) {
     constexpr int VN = Vec<T>::n;
+    const int B = BC ? BC : B_arg;
     const int vpr = d / VN;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t t = idx / vpr;
     const int cv = (int)(idx % vpr);
     if (t >= n_out_total) return;
     const T *in = static_cast<const T *>(a.in[blockIdx.y]) + (t * B) * (int64_t)d + cv * VN;
-    float s[VN], x[VN];
+    float s[VN];
 #pragma unroll
     for (int e = 0; e < VN; ++e) s[e] = 0.f;
-    for (int r = 0; r < B; ++r) {
-        load_vec<T>(in + (int64_t)r * d, x);
+    if constexpr (BC != 0) {
+        float x[BC][VN];
 #pragma unroll
-        for (int e = 0; e < VN; ++e) s[e] = s[e] + x[e];
+        for (int r = 0; r < BC; ++r) load_vec<T>(in + (int64_t)r * d, x[r]);
+#pragma unroll
+        for (int r = 0; r < BC; ++r)
+#pragma unroll
+            for (int e = 0; e < VN; ++e) s[e] = s[e] + x[r][e];
+    } else {
+        float x[VN];
+        for (int r = 0; r < B; ++r) {
+            load_vec<T>(in + (int64_t)r * d, x);
+#pragma unroll
+            for (int e = 0; e < VN; ++e) s[e] = s[e] + x[e];
+        }
     }
     const float Bf = (float)B;
 #pragma unroll
@@ -120,8 +134,9 @@ hipError_t launch_pool(const Plan &p, const void *Q, const void *K, const void *
         const int vn = 16 / p.elt;
         const int64_t threads = n_out_total * (p.d / vn);
         dim3 grid((unsigned)((threads + 255) / 256), cnt);
-        if (p.elt == 4) pool_kernel<float><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
-        else            pool_kernel<bf16_t><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        if (p.elt == 4) pool_kernel<float, 0><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else if (p.B == 16) pool_kernel<bf16_t, 16><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else                pool_kernel<bf16_t, 0><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
