@@ -112,7 +112,7 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
     // coarse-level dK/dV grouped by level-1 query block: d = 64, whole groups of 256 queries, short lists
     int coarse_blocks = 0;
     for (int l = 1; l <= dkv_group_top(p); ++l) coarse_blocks += (l < p.L) ? p.Kl[l] : (int)((p.n[l] + 15) / 16);
-    p.group = p.fast && d.d == 64 && d.N % 256 == 0 && p.Le >= 1 && coarse_blocks <= 512 && dkv_group_top(p) >= 1;
+    p.group = p.fast && d.N % 256 == 0 && p.Le >= 1 && coarse_blocks <= 512 && dkv_group_top(p) >= 1;
     p.grp_slab_off = p.grp_red_off[0] = p.grp_red_off[1] = ws;
     if (p.group) {
         size_t slab = 0, red = 0;

@@ -83,6 +83,12 @@ def test_config1_n4096_bf16_all_heads():
     dict(name="three_supergroups", batch=1, heads=2, d=64, N=12288, B=16, K=3, L=3, dtype="bf16", kind="gaussian"),
     # four coarse levels with a one-token top: 13 listed blocks at levels 2 and 3 (two per wave, some waves one)
     dict(name="K12_L4", batch=1, heads=1, d=64, N=65536, B=16, K=12, L=4, Le=4, dtype="bf16", kind="gaussian"),
+    # d = 128 with sparse levels 1 and 2 grouped by query block (3 listed blocks each) and the dense top of 3 tokens
+    # left to the split kernel; then the same geometry with the list stopping at level 2
+    dict(name="three_supergroups_d128", batch=1, heads=2, d=128, N=12288, B=16, K=3, L=3, dtype="bf16", kind="gaussian"),
+    dict(name="Le2_d128", batch=1, heads=1, d=128, N=12288, B=16, K=3, L=3, Le=2, dtype="bf16", kind="gaussian"),
+    # d = 128, 11 listed blocks at level 2: two launches of the upper-level kernel, the second with 3 of 8 waves busy
+    dict(name="K11_d128", batch=1, heads=1, d=128, N=65536, B=16, K=11, L=3, dtype="bf16", kind="gaussian"),
 ])
 def test_edge_shapes(cfg):
     _full_parity(cfg, 0x5EED0 + len(cfg["name"]))
