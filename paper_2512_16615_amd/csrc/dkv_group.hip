@@ -531,7 +531,7 @@ static hipError_t launch_group_kernel(const Plan &p, const LevelTable &t, const 
 
 hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
                             const float *D, void *ws, hipStream_t s, hipStream_t side, hipEvent_t ev_fork,
-                            hipEvent_t ev_join) {
+                            hipEvent_t ev_join, hipEvent_t lists) {
     char *w = static_cast<char *>(ws);
     const int64_t NR = p.N / 256;
     const int top = dkv_group_top(p), G = upper_G(p);
@@ -550,6 +550,7 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
     if (!G) {                                               // one kernel for every level, then top-down (a level adds the share of the one above)
         a.lev_end = top + 1;
         GRP_TRY(launch_group_kernel(p, t, a, s));
+        if (lists) GRP_TRY(hipStreamWaitEvent(s, lists, 0));          // the gathers read the lists
         for (int l = top; l >= 1; --l) GRP_TRY(finish_level(p, t, a, l, groups[l], w, s));
         return hipSuccess;
     }
@@ -577,7 +578,8 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
 
     a.lev_end = 2;
     GRP_TRY(launch_group_kernel(p, t, a, s));
-    if (fork) GRP_TRY(hipStreamWaitEvent(s, ev_join, 0));
+    if (fork) GRP_TRY(hipStreamWaitEvent(s, ev_join, 0));           // `side` is in order: the lists are complete too
+    else if (lists) GRP_TRY(hipStreamWaitEvent(s, lists, 0));
     return finish_level(p, t, a, 1, groups[1], w, s);     // level 1 has no reduction, so the buffers are free of a race
 }
 

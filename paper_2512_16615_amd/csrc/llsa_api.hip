@@ -353,14 +353,18 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, O, dO, LSE, D, dQ, s));
         else LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
     }
-    if (aux) LLSA_TRY(hipStreamWaitEvent(s, aux->ev[1], 0));   // the key-major lists are ready from here on
+    // The caller's stream waits for the key-major lists only where it first reads them: the grouped kernels
+    // write per-query-block partials and need no list, so they start right behind dQ.
+    hipEvent_t lists = aux ? aux->ev[1] : nullptr;
+    const bool lists_late = lists && p.group && dkv_group_top(p) == p.Le;
+    if (lists && !lists_late) LLSA_TRY(hipStreamWaitEvent(s, lists, 0));
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
     {
         StageScope sc(kDkvCoarse, call, s);
         if (p.group) {                                      // levels above the grouped kernel's range first
             for (int l = p.Le; l > dkv_group_top(p); --l) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
             LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, side, aux ? aux->ev[2] : nullptr,
-                                      aux ? aux->ev[3] : nullptr));
+                                      aux ? aux->ev[3] : nullptr, lists_late ? lists : nullptr));
         } else for (int l = p.Le; l >= 1; --l) {
             if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
             else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
