@@ -49,15 +49,7 @@ struct GroupArgs {
     float sc2, scale;
 };
 
-// ---- the staged group: 256 rows of Q and of dO, unpadded, 16-byte chunks XOR-swizzled by row.
-// d = 64 (128-byte rows, half a row of the 64 LDS banks): the key gives the 16 rows of a slice 8 distinct values per
-// row parity, so the row-wise 16-byte reads of 16 lanes hit 16 different bank groups.  (A key that also spreads the
-// transposed 8-byte reads of a half wave was timed: those reads did not get faster, the row-wise ones got slower.)
-// d = 128 (256-byte rows, all banks): the key is a bijection of the 16 rows of a slice onto the 16 chunks, and its
-// upper three bits differ among the 8 rows a half wave reads transposed.
-template <int D> __device__ __forceinline__ int swz_key(int r) {
-    return D == 64 ? ((r >> 1) & 7) : (((r & 7) << 1) | ((r >> 3) & 1));
-}
+// ---- the staged group: 256 rows of Q and of dO, unpadded, 16-byte chunks XOR-swizzled by row (swz_key)
 template <int D> __device__ __forceinline__ int swz(int r, int c) { return r * GShape<D>::ROWB + ((c ^ swz_key<D>(r)) << 4); }
 
 // The 256 Q and dO rows from row0 on, and their LSE and D, in the registers of NTHR threads ...

@@ -237,7 +237,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 constexpr int kSoloMax = 24;                                // longest list (entries) one wave takes alone
 
 template <int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 1))) dkv_fine_kernel(DkvArgs a) {
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2))) dkv_fine_kernel(DkvArgs a) {
     using S = DkvShape<D>;
     __shared__ __attribute__((aligned(16))) char lds[4][2 * S::TILE + 256];
     __shared__ int len_sh[4];

@@ -79,6 +79,16 @@ __device__ __forceinline__ T pick(const T (&arr)[n], int idx) {
     return v;
 }
 
+// Rows of D bf16 kept unpadded in LDS, the 16-byte chunk c of row r stored at chunk c ^ swz_key(r).
+// d = 64 (128-byte rows, half a row of the 64 LDS banks): the key gives 16 consecutive rows 8 distinct values per
+// row parity, so the row-wise 16-byte reads of 16 lanes hit 16 different bank groups.  (A key that also spreads the
+// transposed 8-byte reads of a half wave was timed: those reads did not get faster, the row-wise ones got slower.)
+// d = 128 (256-byte rows, all banks): the key is a bijection of 16 consecutive rows onto the 16 chunks, and its
+// upper three bits differ among the 8 rows a half wave reads transposed.
+template <int D> __device__ __forceinline__ int swz_key(int r) {
+    return D == 64 ? ((r >> 1) & 7) : (((r & 7) << 1) | ((r >> 3) & 1));
+}
+
 // Workgroup id -> work item so that the workgroups one XCD receives (ids congruent modulo 8) cover a
 // contiguous range of work items: neighbouring query blocks gather overlapping keys, which then stay in
 // that XCD's L2.
