@@ -1,5 +1,5 @@
-// Hierarchical Top-K selection, one level (Alg. 1, selection loop), fast path for bf16, B = 16, at most
-// 256 candidates per query block and K <= 16.
+// Hierarchical Top-K selection, one level (Alg. 1, selection loop), fast path for bf16, B = 16 and K <= 16: at most
+// 256 candidates per query block (select_fast_kernel) or a coarsest level of any length (select_dense_kernel).
 //
 // One workgroup (256 threads) per level-l query block of 16 query tokens.  The candidate key rows (all
 // n_L tokens at the coarsest level, the 16 * K_l children of the parent's picks below it) and the 16
@@ -97,21 +97,108 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
     }
 }
 
+// The coarsest level when it has more than 256 tokens (few levels for the sequence length, or the single-level
+// method of Sec. 3.2): every token of the level is a candidate.  Same lane layout; the candidates pass through LDS
+// 256 at a time, and the row group keeps its K best so far (lane k: the k-th best), which compete in the next
+// chunk's rounds as one more candidate per lane.  Their key ids are lower than the chunk's, so the tie rule holds.
+template <int D>
+__global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
+                                                            int64_t n_l, int Kout, int32_t *__restrict__ out, int64_t nblk) {
+    constexpr int STRIDE = 2 * D + 16, CH = D / 8, MC = 16;
+    __shared__ __attribute__((aligned(16))) char kc[256 * STRIDE];
+    __shared__ __attribute__((aligned(16))) char qs[16 * STRIDE];
+
+    const int tid = threadIdx.x;
+    const int64_t bh = blockIdx.x / nblk, r = blockIdx.x % nblk;
+    const uint16_t *Kb = Kl + bh * n_l * D;
+    for (int c = tid; c < 16 * CH; c += 256) {
+        const int u = c / CH, part = c % CH;
+        const int64_t i = min(r * 16 + u, n_l - 1);
+        *reinterpret_cast<u32x4 *>(qs + u * STRIDE + part * 16) =
+            *reinterpret_cast<const u32x4 *>(Ql + (bh * n_l + i) * D + part * 8);
+    }
+    const int cg = tid & 15, row = tid >> 4;
+    constexpr int kNone = 0x7fffffff;
+    float best_s = -INFINITY;                               // lane k of the row group: k-th best so far and its key id
+    int best_id = kNone;
+    for (int64_t c0 = 0; c0 < n_l; c0 += 256) {
+        __syncthreads();                                    // the previous chunk has been scored
+        for (int c = tid; c < 256 * CH; c += 256) {
+            const int p = c / CH, part = c % CH;
+            const int64_t id = min(c0 + p, n_l - 1);
+            *reinterpret_cast<u32x4 *>(kc + p * STRIDE + part * 16) = *reinterpret_cast<const u32x4 *>(Kb + id * D + part * 8);
+        }
+        __syncthreads();
+        float sc[MC];
+#pragma unroll
+        for (int m = 0; m < MC; ++m) sc[m] = 0.f;
+        for (int ch = 0; ch < CH; ++ch) {
+            float q[8];
+            unpack8(*reinterpret_cast<const u32x4 *>(qs + row * STRIDE + ch * 16), q);
+#pragma unroll
+            for (int m = 0; m < MC; ++m) {
+                float k[8];
+                unpack8(*reinterpret_cast<const u32x4 *>(kc + (cg + 16 * m) * STRIDE + ch * 16), k);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sc[m] = __builtin_fmaf(q[e], k[e], sc[m]);
+            }
+        }
+        const int id0 = (int)c0 + cg;                       // key id of sc[m]: id0 + 16 m
+#pragma unroll
+        for (int m = 0; m < MC; ++m)
+            if (id0 + 16 * m >= n_l) sc[m] = -INFINITY;
+
+        float old_s = best_s, new_s = -INFINITY;            // this lane's entry of the running list competes too
+        int old_id = best_id, new_id = kNone;
+        for (int k = 0; k < Kout; ++k) {
+            float bs = old_s;
+            int bp = old_id;
+#pragma unroll
+            for (int m = 0; m < MC; ++m)
+                if (sc[m] > bs) { bs = sc[m]; bp = id0 + 16 * m; }   // ascending ids: strict '>' keeps the lowest
+#pragma unroll
+            for (int o = 8; o >= 1; o >>= 1) {
+                const float os = __shfl_xor(bs, o, 16);
+                const int op = __shfl_xor(bp, o, 16);
+                if (os > bs || (os == bs && op < bp)) { bs = os; bp = op; }
+            }
+            if (bp == old_id) { old_s = -INFINITY; old_id = kNone; }
+#pragma unroll
+            for (int m = 0; m < MC; ++m)
+                if (bp == id0 + 16 * m) sc[m] = -INFINITY;
+            if (cg == k) { new_s = bs; new_id = bp; }
+        }
+        best_s = new_s;
+        best_id = new_id;
+    }
+    int rank = 0;                                           // rows are written in ascending id order
+    for (int k = 0; k < Kout; ++k) rank += (__shfl(best_id, k, 16) < best_id) ? 1 : 0;
+    const int64_t i = r * 16 + row;
+    if (cg < Kout && i < n_l) out[(bh * n_l + i) * Kout + rank] = best_id;
+}
+
 // true if the fast kernel covers this level
 bool select_fast_ok(const Plan &p, int l) {
     const int64_t C = (l == p.L) ? p.n[l] : (int64_t)p.Kl[l] * p.B;
-    return p.elt == 2 && p.B == 16 && (p.d == 64 || p.d == 128) && C <= 256 && p.Kl[l - 1] <= 16;
+    const bool dense_top = (l == p.L);                      // any number of candidates, 256 at a time
+    return p.elt == 2 && p.B == 16 && (p.d == 64 || p.d == 128) && (C <= 256 || dense_top) && p.Kl[l - 1] <= 16 &&
+           p.n[l] < ((int64_t)1 << 30);
 }
 
 hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s) {
     const char *w = static_cast<const char *>(ws);
     const bool top = (l == p.L);
-    const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
     const int64_t nblk = (p.n[l] + 15) / 16;
     const uint16_t *Ql = (const uint16_t *)(w + p.pyr_off[0][l]), *Kl = (const uint16_t *)(w + p.pyr_off[1][l]);
     const int32_t *par = top ? nullptr : parent;
     const int Kp = top ? 0 : p.Kl[l], Kout = p.Kl[l - 1];
     dim3 grid((unsigned)(p.bh * nblk));
+    if (top && p.n[l] > 256) {
+        if (p.d == 64) select_dense_kernel<64><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], Kout, out, nblk);
+        else select_dense_kernel<128><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], Kout, out, nblk);
+        return hipGetLastError();
+    }
+    const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
     if (p.d == 64) {
         if (C <= 128) select_fast_kernel<64, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
         else select_fast_kernel<64, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);

@@ -89,6 +89,11 @@ def test_config1_n4096_bf16_all_heads():
     dict(name="Le2_d128", batch=1, heads=1, d=128, N=12288, B=16, K=3, L=3, Le=2, dtype="bf16", kind="gaussian"),
     # d = 128, 11 listed blocks at level 2: two launches of the upper-level kernel, the second with 3 of 8 waves busy
     dict(name="K11_d128", batch=1, heads=1, d=128, N=65536, B=16, K=11, L=3, dtype="bf16", kind="gaussian"),
+    # single-level method with a coarsest level of 260 tokens: the selection takes its candidates 256 at a time (second
+    # chunk: 4 candidates; last query block: 4 rows); then two full chunks at d = 128 and a top level of 272 under L = 2
+    dict(name="dense_top_260", batch=1, heads=2, d=64, N=4160, B=16, K=8, L=1, dtype="bf16", kind="gaussian"),
+    dict(name="dense_top_512_d128", batch=1, heads=1, d=128, N=8192, B=16, K=16, L=1, dtype="bf16", kind="gaussian"),
+    dict(name="dense_top_272_L2", batch=1, heads=1, d=64, N=69632, B=16, K=4, L=2, dtype="bf16", kind="gaussian"),
 ])
 def test_edge_shapes(cfg):
     _full_parity(cfg, 0x5EED0 + len(cfg["name"]))
