@@ -192,6 +192,9 @@ def sweep_cases(which):
     if which in ("K", "all"):
         for K in (4, 8, 16, 32):
             add("K", 65536, 3, K=K)
+    if which in ("B", "all"):                                  # the paper's other block size (Fig. 3), same tokens per level
+        out.append(("B", dict(base, name="B_N65536_B64_L2_K2", N=65536, B=64, L=2, K=2, heads=16), None))
+        out.append(("B", dict(base, name="B_N65536_B64_L2_K8", N=65536, B=64, L=2, K=8, heads=16), None))
     return out
 
 
@@ -252,7 +255,7 @@ def main():
                     help="keep the backward on the caller's stream (no fork onto the plan's auxiliary stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 512 MiB (to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--sweep", default=None, choices=["n", "L", "Le", "K", "all"],
+    ap.add_argument("--sweep", default=None, choices=["n", "L", "Le", "K", "B", "all"],
                     help="run the shape sweep instead of the headline workload")
     args = ap.parse_args()
     if args.gpus != 1:

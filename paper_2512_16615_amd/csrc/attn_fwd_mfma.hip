@@ -167,7 +167,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                 hipStream_t s) {
-    if (p.N % 256 == 0) return launch_attn_fwd_shared(p, t, Q, O, LSE, s);
+    if (p.N % 256 == 0 && (p.Kl[0] << (p.lb - 4)) <= 64) return launch_attn_fwd_shared(p, t, Q, O, LSE, s);
     const int64_t wgs = (int64_t)p.bh * (p.N / 64);                  // 4 query blocks per workgroup
     dim3 grid((unsigned)wgs);
     if (p.d == 64)

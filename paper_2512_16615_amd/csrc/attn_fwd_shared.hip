@@ -1,5 +1,5 @@
 // Attention forward over the gathered lists on bf16 MFMA, variant that shares the coarse levels
-// (B = 16, d = 64 or 128, N a multiple of 256).
+// (B = 16, 32 or 64, d = 64 or 128, N a multiple of 256, at most 64 level-0 tiles of 16 tokens per list).
 //
 // The 16 fine query blocks under one level-1 query block use the same lists at every level >= 1 (Alg. 1,
 // enrichment loop: block i reads row i / B^l of I^(l)), i.e. the same coarse key/value tokens.  One
@@ -123,12 +123,16 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
     using B1 = std::integral_constant<int, 1>;
 
     // The level-0 lists of this wave's NB query blocks, fetched now so that phase B does not wait for them:
-    // lane (64 / NB) b + j holds the first token of block j of query block b's list (K_0 <= 64 / NB).
-    const int nb0 = t.bseg[1];                                        // K_0 (the list always holds level 0)
+    // lane (64 / NB) b + j holds the first token of 16-token tile j of query tile b's list (at most 64 / NB tiles;
+    // a listed block of B tokens is B / 16 consecutive tiles, and B / 16 consecutive query tiles share a row of I^(0)).
+    const int nb0 = t.bseg[1];                                        // level-0 tiles (the list always holds level 0)
     int tok0 = 0;
     {
         const int b = lane / (64 / NB), j = lane % (64 / NB);
-        if (j < nb0) tok0 = t.I[0][(bh * t.rows[0] + blk0 + NB * wave + b) * t.Kl[0] + j] * 16;
+        if (j < nb0) {
+            const int64_t row = (blk0 + NB * wave + b) >> t.ls;
+            tok0 = (t.I[0][(bh * t.rows[0] + row) * t.Kl[0] + (j >> t.ls)] << t.lb) + ((j & ((1 << t.ls) - 1)) << 4);
+        }
     }
 
     // ------------------------------------------------------------------ phase A: shared coarse levels
@@ -272,7 +276,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 
 hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                   hipStream_t s) {
-    if (p.d == 64 && p.Kl[0] <= 32) {                 // two query blocks per wave (measured faster than one): 16 per workgroup
+    if (p.d == 64 && (p.Kl[0] << (p.lb - 4)) <= 32) { // two query blocks per wave (measured faster than one): 16 per workgroup
         const int64_t wgs = (int64_t)p.bh * (p.N / 256);
         attn_fwd_shared_kernel<64, 2><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N,
                                                                            wgs);

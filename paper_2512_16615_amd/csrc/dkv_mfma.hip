@@ -29,7 +29,9 @@ struct DkvArgs {
     const float *parK, *parV;             // level-1 totals [bh, n_1, D] fp32 or null (level 0)
     uint16_t *dK, *dV;                    // level-0 outputs
     int64_t N, n_l, rows, slab;           // rows = key blocks of this level per head that have lists
-    int span_shift;                       // log2 of the 16-query groups per listed query block = 4 * level
+    int span_shift;                       // log2 of the 16-query groups per listed query block: log2(B^(level+1) / 16)
+    int ls, lb;                           // log2(B / 16), log2 B: 16-key tile j lies in listed block j >> ls
+    float inv_B;
     int Kl_cnt, dense, splits;
     float sc2, bias2, scale;
 };
@@ -208,7 +210,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     if (a.dense) {
         groups = a.N >> 4;
     } else {
-        const int32_t *Crow = a.C + bh * (a.rows + 1) + j;
+        const int32_t *Crow = a.C + bh * (a.rows + 1) + (j >> a.ls);
         const int32_t beg = Crow[0], end = Crow[1];
         lst = a.Iq + bh * a.rows * a.Kl_cnt + beg;
         groups = (int64_t)(end - beg) << a.span_shift;
@@ -234,7 +236,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 }
 
 // ---------------------------------------------------------------------------------------------- level 0
-constexpr int kSoloMax = 24;                                // longest list (entries) one wave takes alone
+constexpr int kSoloMax = 24;                                // longest list (16-query groups) one wave takes alone
 
 template <int D>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2))) dkv_fine_kernel(DkvArgs a) {
@@ -263,8 +265,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     auto par_fetch = [&](int64_t j) {
 #pragma unroll
         for (int x = 0; x < D / 64; ++x) {
-            park[x] = has_par ? a.parK[(bh * nkb + j) * D + lane + 64 * x] : 0.f;
-            parv[x] = has_par ? a.parV[(bh * nkb + j) * D + lane + 64 * x] : 0.f;
+            park[x] = has_par ? a.parK[(bh * (nkb >> a.ls) + (j >> a.ls)) * D + lane + 64 * x] : 0.f;
+            parv[x] = has_par ? a.parV[(bh * (nkb >> a.ls) + (j >> a.ls)) * D + lane + 64 * x] : 0.f;
         }
     };
     auto par_publish = [&]() {                              // the wave's own row; its LDS operations stay in order
@@ -286,7 +288,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         if (has_par) {
             const f32x4 pv = *reinterpret_cast<const f32x4 *>(&par_sh[wave][(isV ? D : 0) + col]);
 #pragma unroll
-            for (int r = 0; r < 4; ++r) sum[r] += pv[r] * 0.0625f;
+            for (int r = 0; r < 4; ++r) sum[r] += pv[r] * a.inv_B;
         }
         u32x2 w;
         w[0] = pack_bf16(sum[0], sum[1]);
@@ -297,8 +299,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
     // ---- each wave alone on its own key block, if that block's list is short
     {
         const int64_t j = kb0 % nkb + wave;
-        const int32_t *Crow = a.C + bh * (a.rows + 1) + j;
-        const int32_t beg = Crow[0], len = Crow[1] - beg;
+        const int32_t *Crow = a.C + bh * (a.rows + 1) + (j >> a.ls);
+        const int32_t beg = Crow[0], len = (Crow[1] - beg) << a.span_shift;   // in 16-query groups
         if (lane == 0) len_sh[wave] = len;
         if (len <= kSoloMax) {
             bf16x8 kop[S::KS], vop[S::KS];
@@ -322,7 +324,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
         const int len = len_sh[w];
         if (len <= kSoloMax) continue;                      // uniform over the workgroup
         const int64_t j = kb0 % nkb + w;
-        const int32_t beg = a.C[bh * (a.rows + 1) + j];
+        const int32_t beg = a.C[bh * (a.rows + 1) + (j >> a.ls)];
         bf16x8 kop[S::KS], vop[S::KS];
         f32x4 accK[S::NT], accV[S::NT];
 #pragma unroll
@@ -339,11 +341,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 }
 
 // Adds the split slabs of one coarse level in split order and, if there is a coarser level above it,
-// that level's share (adjoint of mean pooling, 1/16 of the parent token): dst[t] = sum_s part[s][t]
-// (+ up[t / 16] / 16).  dst is the level's fp32 gradient buffer.  One thread per 4 consecutive floats.
+// that level's share (adjoint of mean pooling, 1/B of the parent token): dst[t] = sum_s part[s][t]
+// (+ up[t / B] / B).  dst is the level's fp32 gradient buffer.  One thread per 4 consecutive floats.
 __global__ void __launch_bounds__(256) dkv_reduce_kernel(const float *partK, const float *partV, float *dstK,
                                                           float *dstV, const float *upK, const float *upV,
-                                                          int64_t total4, int64_t slab, int splits, int d) {
+                                                          int64_t total4, int64_t slab, int splits, int d, int lb,
+                                                          float inv_B) {
     const int64_t i4 = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i4 >= total4) return;
     const int64_t i = i4 * 4;
@@ -354,8 +357,8 @@ __global__ void __launch_bounds__(256) dkv_reduce_kernel(const float *partK, con
     }
     if (upK) {
         const int64_t tok = i / d, c = i % d;
-        k += *reinterpret_cast<const f32x4 *>(upK + (tok >> 4) * d + c) * 0.0625f;
-        v += *reinterpret_cast<const f32x4 *>(upV + (tok >> 4) * d + c) * 0.0625f;
+        k += *reinterpret_cast<const f32x4 *>(upK + (tok >> lb) * d + c) * inv_B;
+        v += *reinterpret_cast<const f32x4 *>(upV + (tok >> lb) * d + c) * inv_B;
     }
     *reinterpret_cast<f32x4 *>(dstK + i) = k;
     *reinterpret_cast<f32x4 *>(dstV + i) = v;
@@ -394,7 +397,8 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
     a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;
     a.N = p.N; a.n_l = p.n[l];
     a.rows = a.dense ? 0 : p.n[l + 1];
-    a.span_shift = a.dense ? 0 : 4 * l;
+    a.span_shift = a.dense ? 0 : p.lb * (l + 1) - 4;
+    a.ls = p.lb - 4; a.lb = p.lb; a.inv_B = 1.f / (float)p.B;
     a.Kl_cnt = a.dense ? 0 : p.Kl[l];
     a.sc2 = p.scale * kLog2e; a.bias2 = t.bias[l] * kLog2e; a.scale = p.scale;
     if (l == 0) {                                           // N % 64 == 0: four key blocks per workgroup, one head
@@ -414,7 +418,7 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
     dkv_reduce_kernel<<<(unsigned)((total4 + 255) / 256), 256, 0, s>>>(
         a.partK, a.partV, (float *)(w + p.dKacc_off[l]), (float *)(w + p.dVacc_off[l]),
         has_up ? (const float *)(w + p.dKacc_off[l + 1]) : nullptr, has_up ? (const float *)(w + p.dVacc_off[l + 1]) : nullptr,
-        total4, a.slab, a.splits, p.d);
+        total4, a.slab, a.splits, p.d, p.lb, 1.f / (float)p.B);
     return hipGetLastError();
 }
 

@@ -151,7 +151,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(D == 6
 
 hipError_t launch_dq_mfma(const Plan &p, const LevelTable &t, const void *Q, const void *O, const void *dO,
                           const float *LSE, float *D, void *dQ, hipStream_t s) {
-    if (p.N % 256 == 0) return launch_dq_shared(p, t, Q, O, dO, LSE, D, dQ, s);
+    if (p.N % 256 == 0 && (p.Kl[0] << (p.lb - 4)) <= 64) return launch_dq_shared(p, t, Q, O, dO, LSE, D, dQ, s);
     const int64_t wgs = (int64_t)p.bh * (p.N / 64);
     dim3 grid((unsigned)wgs);
     if (p.d == 64)

@@ -106,8 +106,18 @@ __global__ void __launch_bounds__(256) pool_kernel(PoolArgs a, int64_t n_out_tot
 #pragma unroll
             for (int e = 0; e < VN; ++e) s[e] = s[e] + x[r][e];
     } else {
+        int r0 = 0;
+        for (; r0 + 16 <= B; r0 += 16) {                   // 16 rows in flight at a time, added in row order
+            float x[16][VN];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) load_vec<T>(in + (int64_t)(r0 + r) * d, x[r]);
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+#pragma unroll
+                for (int e = 0; e < VN; ++e) s[e] = s[e] + x[r][e];
+        }
         float x[VN];
-        for (int r = 0; r < B; ++r) {
+        for (int r = r0; r < B; ++r) {
             load_vec<T>(in + (int64_t)r * d, x);
 #pragma unroll
             for (int e = 0; e < VN; ++e) s[e] = s[e] + x[e];

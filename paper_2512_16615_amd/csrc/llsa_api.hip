@@ -34,7 +34,7 @@ LevelTable make_level_table(const Plan &p, const void *K0, const void *V0, const
             t.seg[l] = pos;
             pos += (l < p.L) ? p.Kl[l] * p.B : (int)p.n[l];
             t.bseg[l] = bpos;
-            bpos += (l < p.L) ? p.Kl[l] : (int)((p.n[l] + 15) / 16);
+            bpos += (l < p.L) ? p.Kl[l] * ((p.B + 15) / 16) : (int)((p.n[l] + 15) / 16);
         }
         bp *= p.B;
     }
@@ -44,6 +44,8 @@ LevelTable make_level_table(const Plan &p, const void *K0, const void *V0, const
     t.bseg[t.nlev] = bpos;
     t.L = p.L;
     t.B = p.B;
+    t.lb = p.lb;
+    t.ls = p.lb >= 4 ? p.lb - 4 : 0;
     t.d = p.d;
     t.scale = p.scale;
     return t;
@@ -107,12 +109,14 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
         p.dKacc_off[l] = ws; ws = align_up(ws + bytes);
         p.dVacc_off[l] = ws; ws = align_up(ws + bytes);
     }
-    // MFMA kernels: bf16, B = 16, d = 64 / 128, and whole workgroups of 4 query blocks per head
-    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && d.B == 16 && (d.d == 64 || d.d == 128) && d.N % 64 == 0;
+    // MFMA kernels: bf16, blocks of 1, 2 or 4 16-token tiles, d = 64 / 128, and whole workgroups of 4 query tiles per head
+    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && (d.B == 16 || d.B == 32 || d.B == 64) &&
+             (d.d == 64 || d.d == 128) && d.N % 64 == 0;
+    p.lb = !p.fast ? 0 : d.B == 16 ? 4 : d.B == 32 ? 5 : 6;
     // coarse-level dK/dV grouped by level-1 query block: d = 64, whole groups of 256 queries, short lists
     int coarse_blocks = 0;
     for (int l = 1; l <= dkv_group_top(p); ++l) coarse_blocks += (l < p.L) ? p.Kl[l] : (int)((p.n[l] + 15) / 16);
-    p.group = p.fast && d.N % 256 == 0 && p.Le >= 1 && coarse_blocks <= 512 && dkv_group_top(p) >= 1;
+    p.group = p.fast && d.B == 16 && d.N % 256 == 0 && p.Le >= 1 && coarse_blocks <= 512 && dkv_group_top(p) >= 1;
     p.grp_slab_off = p.grp_red_off[0] = p.grp_red_off[1] = ws;
     if (p.group) {
         size_t slab = 0, red = 0;

@@ -30,7 +30,8 @@ struct Plan {
     bool group;                     // coarse levels' dK/dV run grouped by level-1 query block
     size_t ws_fwd, ws_bwd;
     int list_len;                   // tokens one query attends to
-    bool fast;                      // MFMA kernels apply (bf16, B = 16, d in {64, 128})
+    bool fast;                      // MFMA kernels apply (bf16, B in {16, 32, 64}, d in {64, 128})
+    int lb;                         // log2 B when fast
 };
 
 // What the attention-type kernels need to walk the gathered list of a query block.
@@ -47,6 +48,7 @@ struct LevelTable {
     float bias[kMaxL + 1];          // l * ln B (or 0)
     int nlev;                       // levels in the list = Le + 1
     int L, B, d;
+    int lb, ls;                     // log2 B and log2(B / 16) when B is 16, 32 or 64 (MFMA kernels), else 0
     float scale;
 };
 

@@ -97,8 +97,9 @@ __device__ __forceinline__ int64_t xcd_contiguous(int64_t w, int64_t total) {
     return (w < per * 8) ? (w & 7) * per + (w >> 3) : w;
 }
 
-// The 16-token key blocks of one fine query block's list (Alg. 1, enrichment loop; B = 16), 64 at a time:
-// lane j of the wave describes block 64 * chunk + j.  The main loops fetch a block's fields with
+// The 16-token key tiles of one 16-query tile's list (Alg. 1, enrichment loop), 64 at a time: lane j of the wave
+// describes tile 64 * chunk + j.  A listed block of B = 16 * 2^ls tokens is 2^ls consecutive tiles; query tile `blk`
+// (queries 16 blk ...) reads row 16 blk / B^(l+1) of I^(l).  The main loops fetch a block's fields with
 // v_readlane (block numbers are wave-uniform), which keeps the per-tile scalar work small.
 struct BlockTable {
     uint64_t kptr, vptr;     // address of the block's first key / value row
@@ -121,8 +122,9 @@ struct BlockTable {
                 const int k = jb - b0;
                 int64_t tok0;
                 if (l < t.L) {
-                    const int64_t row = blk >> (4 * l);
-                    tok0 = (int64_t)pick(t.I, l)[(bh * pick(t.rows, l) + row) * pick(t.Kl, l) + k] * 16;
+                    const int64_t row = blk >> (t.lb * (l + 1) - 4);
+                    const int32_t listed = pick(t.I, l)[(bh * pick(t.rows, l) + row) * pick(t.Kl, l) + (k >> t.ls)];
+                    tok0 = ((int64_t)listed << t.lb) + ((k & ((1 << t.ls) - 1)) << 4);
                     cnt = 16;
                 } else {
                     tok0 = (int64_t)k * 16;

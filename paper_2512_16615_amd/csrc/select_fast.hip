@@ -1,5 +1,5 @@
-// Hierarchical Top-K selection, one level (Alg. 1, selection loop), fast path for bf16, B = 16 and K <= 16: at most
-// 256 candidates per query block (select_fast_kernel) or a coarsest level of any length (select_dense_kernel).
+// Hierarchical Top-K selection, one level (Alg. 1, selection loop), fast path for bf16, B in {16, 32, 64} and
+// K <= 16: at most 256 candidates per query tile (select_fast_kernel) or any number (select_dense_kernel).
 //
 // One workgroup (256 threads) per level-l query block of 16 query tokens.  The candidate key rows (all
 // n_L tokens at the coarsest level, the 16 * K_l children of the parent's picks below it) and the 16
@@ -23,7 +23,8 @@ __device__ __forceinline__ void unpack8(u32x4 w, float *f) {
 template <int D, int MC>
 __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
                                                            int64_t n_l, const int32_t *__restrict__ parent, int Kp,
-                                                           int Kout, int32_t *__restrict__ out, int C, int64_t nblk) {
+                                                           int Kout, int32_t *__restrict__ out, int C, int64_t nblk,
+                                                           int lb) {
     constexpr int STRIDE = 2 * D + 16;                      // bytes per staged row: keeps 16-byte reads conflict-free
     constexpr int CH = D / 8;                               // 16-byte chunks per row
     __shared__ __attribute__((aligned(16))) char kc[16 * MC * STRIDE];
@@ -32,12 +33,15 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
     const int tid = threadIdx.x;
     const int64_t bh = blockIdx.x / nblk, r = blockIdx.x % nblk;
     const uint16_t *Kb = Kl + bh * n_l * D;
-    const int32_t *prow = parent ? parent + (bh * nblk + r) * Kp : nullptr;
+    // the 16 query tokens lie in one block of B = 2^lb tokens: row (16 r) / B of the parent list, whose picks'
+    // B children each are the candidates
+    const int Bm1 = (1 << lb) - 1;
+    const int32_t *prow = parent ? parent + (bh * (n_l >> lb) + (r >> (lb - 4))) * Kp : nullptr;
 
     // stage the candidate rows (16-byte chunks, coalesced within a row) and the query rows
     for (int c = tid; c < C * CH; c += 256) {
         const int p = c / CH, part = c % CH;
-        const int64_t id = prow ? (int64_t)prow[p >> 4] * 16 + (p & 15) : p;
+        const int64_t id = prow ? ((int64_t)prow[p >> lb] << lb) + (p & Bm1) : p;
         *reinterpret_cast<u32x4 *>(kc + p * STRIDE + part * 16) = *reinterpret_cast<const u32x4 *>(Kb + id * D + part * 8);
     }
     for (int c = tid; c < 16 * CH; c += 256) {
@@ -92,18 +96,21 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
     for (int k = 0; k < Kout; ++k) rank += (__shfl(mine, k, 16) < mine) ? 1 : 0;
     const int64_t i = r * 16 + row;
     if (cg < Kout && i < n_l) {
-        const int64_t id = prow ? (int64_t)prow[mine >> 4] * 16 + (mine & 15) : mine;
+        const int64_t id = prow ? ((int64_t)prow[mine >> lb] << lb) + (mine & Bm1) : mine;
         out[(bh * n_l + i) * Kout + rank] = (int32_t)id;
     }
 }
 
-// The coarsest level when it has more than 256 tokens (few levels for the sequence length, or the single-level
-// method of Sec. 3.2): every token of the level is a candidate.  Same lane layout; the candidates pass through LDS
-// 256 at a time, and the row group keeps its K best so far (lane k: the k-th best), which compete in the next
-// chunk's rounds as one more candidate per lane.  Their key ids are lower than the chunk's, so the tie rule holds.
+// More than 256 candidates: a coarsest level of more than 256 tokens (few levels for the sequence length, or the
+// single-level method of Sec. 3.2: every token of the level is a candidate), or more than 256 children of the parent's
+// picks (B = 64, K > 4).  Same lane layout; the C candidates pass through LDS 256 at a time, and the row group
+// keeps its K best so far (lane k: the k-th best), which compete in the next chunk's rounds as one more candidate
+// per lane.  Their key ids are lower than the chunk's (candidate positions ascend with the key id), so the tie
+// rule holds.
 template <int D>
 __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
-                                                            int64_t n_l, int Kout, int32_t *__restrict__ out, int64_t nblk) {
+                                                            int64_t n_l, const int32_t *__restrict__ parent, int Kp, int C,
+                                                            int Kout, int32_t *__restrict__ out, int64_t nblk, int lb) {
     constexpr int STRIDE = 2 * D + 16, CH = D / 8, MC = 16;
     __shared__ __attribute__((aligned(16))) char kc[256 * STRIDE];
     __shared__ __attribute__((aligned(16))) char qs[16 * STRIDE];
@@ -111,6 +118,9 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
     const int tid = threadIdx.x;
     const int64_t bh = blockIdx.x / nblk, r = blockIdx.x % nblk;
     const uint16_t *Kb = Kl + bh * n_l * D;
+    const int Bm1 = (1 << lb) - 1;
+    const int32_t *prow = parent ? parent + (bh * (n_l >> lb) + (r >> (lb - 4))) * Kp : nullptr;
+    auto key_id = [&](int pos) { return prow ? (prow[pos >> lb] << lb) + (pos & Bm1) : pos; };
     for (int c = tid; c < 16 * CH; c += 256) {
         const int u = c / CH, part = c % CH;
         const int64_t i = min(r * 16 + u, n_l - 1);
@@ -121,11 +131,11 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
     constexpr int kNone = 0x7fffffff;
     float best_s = -INFINITY;                               // lane k of the row group: k-th best so far and its key id
     int best_id = kNone;
-    for (int64_t c0 = 0; c0 < n_l; c0 += 256) {
+    for (int c0 = 0; c0 < C; c0 += 256) {
         __syncthreads();                                    // the previous chunk has been scored
         for (int c = tid; c < 256 * CH; c += 256) {
             const int p = c / CH, part = c % CH;
-            const int64_t id = min(c0 + p, n_l - 1);
+            const int64_t id = key_id(min(c0 + p, C - 1));
             *reinterpret_cast<u32x4 *>(kc + p * STRIDE + part * 16) = *reinterpret_cast<const u32x4 *>(Kb + id * D + part * 8);
         }
         __syncthreads();
@@ -143,10 +153,13 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
                 for (int e = 0; e < 8; ++e) sc[m] = __builtin_fmaf(q[e], k[e], sc[m]);
             }
         }
-        const int id0 = (int)c0 + cg;                       // key id of sc[m]: id0 + 16 m
+        const int pos0 = c0 + cg;                           // candidate position of sc[m]: pos0 + 16 m
+        int id[MC];                                         // and its key id (ascending with the position)
 #pragma unroll
-        for (int m = 0; m < MC; ++m)
-            if (id0 + 16 * m >= n_l) sc[m] = -INFINITY;
+        for (int m = 0; m < MC; ++m) {
+            id[m] = pos0 + 16 * m < C ? key_id(pos0 + 16 * m) : kNone;
+            if (pos0 + 16 * m >= C) sc[m] = -INFINITY;
+        }
 
         float old_s = best_s, new_s = -INFINITY;            // this lane's entry of the running list competes too
         int old_id = best_id, new_id = kNone;
@@ -155,7 +168,7 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
             int bp = old_id;
 #pragma unroll
             for (int m = 0; m < MC; ++m)
-                if (sc[m] > bs) { bs = sc[m]; bp = id0 + 16 * m; }   // ascending ids: strict '>' keeps the lowest
+                if (sc[m] > bs) { bs = sc[m]; bp = id[m]; }      // ascending ids: strict '>' keeps the lowest
 #pragma unroll
             for (int o = 8; o >= 1; o >>= 1) {
                 const float os = __shfl_xor(bs, o, 16);
@@ -165,7 +178,7 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
             if (bp == old_id) { old_s = -INFINITY; old_id = kNone; }
 #pragma unroll
             for (int m = 0; m < MC; ++m)
-                if (bp == id0 + 16 * m) sc[m] = -INFINITY;
+                if (bp == id[m]) sc[m] = -INFINITY;
             if (cg == k) { new_s = bs; new_id = bp; }
         }
         best_s = new_s;
@@ -180,9 +193,9 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
 // true if the fast kernel covers this level
 bool select_fast_ok(const Plan &p, int l) {
     const int64_t C = (l == p.L) ? p.n[l] : (int64_t)p.Kl[l] * p.B;
-    const bool dense_top = (l == p.L);                      // any number of candidates, 256 at a time
-    return p.elt == 2 && p.B == 16 && (p.d == 64 || p.d == 128) && (C <= 256 || dense_top) && p.Kl[l - 1] <= 16 &&
-           p.n[l] < ((int64_t)1 << 30);
+    // any number of candidates (256 at a time beyond 256); 16 consecutive query tokens share their candidates
+    return p.fast && p.Kl[l - 1] <= 16 && p.n[l] < ((int64_t)1 << 30) && C < (1 << 30) &&
+           (l == p.L || p.n[l] % 16 == 0);
 }
 
 hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s) {
@@ -193,18 +206,18 @@ hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_
     const int32_t *par = top ? nullptr : parent;
     const int Kp = top ? 0 : p.Kl[l], Kout = p.Kl[l - 1];
     dim3 grid((unsigned)(p.bh * nblk));
-    if (top && p.n[l] > 256) {
-        if (p.d == 64) select_dense_kernel<64><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], Kout, out, nblk);
-        else select_dense_kernel<128><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], Kout, out, nblk);
+    const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
+    if (C > 256) {
+        if (p.d == 64) select_dense_kernel<64><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
+        else select_dense_kernel<128><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
         return hipGetLastError();
     }
-    const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
     if (p.d == 64) {
-        if (C <= 128) select_fast_kernel<64, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
-        else select_fast_kernel<64, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
+        if (C <= 128) select_fast_kernel<64, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        else select_fast_kernel<64, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
     } else {
-        if (C <= 128) select_fast_kernel<128, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
-        else select_fast_kernel<128, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk);
+        if (C <= 128) select_fast_kernel<128, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        else select_fast_kernel<128, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
     }
     return hipGetLastError();
 }

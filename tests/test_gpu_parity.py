@@ -94,6 +94,19 @@ def test_config1_n4096_bf16_all_heads():
     dict(name="dense_top_260", batch=1, heads=2, d=64, N=4160, B=16, K=8, L=1, dtype="bf16", kind="gaussian"),
     dict(name="dense_top_512_d128", batch=1, heads=1, d=128, N=8192, B=16, K=16, L=1, dtype="bf16", kind="gaussian"),
     dict(name="dense_top_272_L2", batch=1, heads=1, d=64, N=69632, B=16, K=4, L=2, dtype="bf16", kind="gaussian"),
+    # blocks of 64 tokens (four 16-token tiles) on the MFMA kernels: one-token top; 512 candidates per selection row
+    # (two chunks) and 32 level-0 tiles per list; 64 level-0 tiles (one query tile per wave); 128 level-0 tiles and
+    # K = 32 (per-wave kernels, portable selection); no enrichment; d = 128
+    dict(name="B64_small", batch=1, heads=2, d=64, N=4096, B=64, K=2, L=2, dtype="bf16", kind="smooth"),
+    dict(name="B64_K8", batch=1, heads=1, d=64, N=65536, B=64, K=8, L=2, dtype="bf16", kind="smooth"),
+    dict(name="B64_K16", batch=1, heads=2, d=64, N=16384, B=64, K=16, L=2, dtype="bf16", kind="gaussian"),
+    dict(name="B64_K32", batch=1, heads=1, d=64, N=16384, B=64, K=32, L=2, dtype="bf16", kind="gaussian"),
+    dict(name="B64_Le0", batch=1, heads=2, d=64, N=16384, B=64, K=4, L=2, Le=0, dtype="bf16", kind="gaussian"),
+    dict(name="B64_d128", batch=2, heads=1, d=128, N=8192, B=64, K=4, L=1, dtype="bf16", kind="gaussian"),
+    # blocks of 32 tokens: three levels with a one-token top; a length that is no multiple of 256 (per-wave kernels)
+    # with a ragged dense level of 66 tokens
+    dict(name="B32_L3", batch=1, heads=2, d=64, N=32768, B=32, K=4, L=3, dtype="bf16", kind="gaussian"),
+    dict(name="B32_ragged", batch=1, heads=2, d=64, N=2112, B=32, K=8, L=1, dtype="bf16", kind="gaussian"),
 ])
 def test_edge_shapes(cfg):
     _full_parity(cfg, 0x5EED0 + len(cfg["name"]))
