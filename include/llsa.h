@@ -61,11 +61,12 @@ typedef struct {
                            given the very workspace llsa_forward filled                     */
     int32_t kernel_path;/* 0: fastest kernels available for the shape; 1: force the portable
                            scalar kernels (any supported shape, used as a cross-check)      */
-    int32_t single_stream; /* 0: llsa_backward may run independent kernels (the index transpose
-                           beside dQ, the upper levels' dK/dV beside level 1's) on one
-                           auxiliary stream the plan owns, forked from and joined back into
-                           the caller's stream inside the call, so the caller sees plain
-                           stream order; 1: everything goes to the caller's stream            */
+    int32_t single_stream; /* 0: llsa_backward may run the index transpose, which depends on
+                           the indices only, on one auxiliary stream the plan owns, beside
+                           kernels that do not read its lists; the stream is forked from
+                           and joined back into the caller's stream inside the call, so
+                           the caller sees plain stream order; 1: everything goes to the
+                           caller's stream                                                  */
 } llsa_desc;
 
 /* Opaque and host-side.  The level table and buffer layout never change after creation.  Unless

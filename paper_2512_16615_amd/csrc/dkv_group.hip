@@ -522,8 +522,7 @@ static hipError_t launch_group_kernel(const Plan &p, const LevelTable &t, const 
 }
 
 hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
-                            const float *D, void *ws, hipStream_t s, hipStream_t side, hipEvent_t ev_fork,
-                            hipEvent_t ev_join, hipEvent_t lists) {
+                            const float *D, void *ws, hipStream_t s, hipEvent_t lists) {
     char *w = static_cast<char *>(ws);
     const int64_t NR = p.N / 256;
     const int top = dkv_group_top(p), G = upper_G(p);
@@ -539,40 +538,27 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
     a.sparse_begin = 0;
     a.do_dense = 0;
 
-    if (!G) {                                               // one kernel for every level, then top-down (a level adds the share of the one above)
-        a.lev_end = top + 1;
-        GRP_TRY(launch_group_kernel(p, t, a, s));
-        if (lists) GRP_TRY(hipStreamWaitEvent(s, lists, 0));          // the gathers read the lists
-        for (int l = top; l >= 1; --l) GRP_TRY(finish_level(p, t, a, l, groups[l], w, s));
-        return hipSuccess;
+    // first the kernels that write the partials (they read no list), then, top-down, the reductions and gathers
+    // (a level adds the share of the one above)
+    if (G) {                                                // levels >= 2 in their own kernel
+        GroupArgs up = a;
+        up.lev_end = top + 1;
+        const dim3 grid((unsigned)(p.bh * (NR / G)));
+        const int per_launch = p.d == 64 ? 16 : 8;          // sparse blocks one launch covers
+        for (int sb = 0; sb == 0 || sb < up.nbs; sb += per_launch) {   // the first launch also takes the dense block (d = 64)
+            up.sparse_begin = sb;
+            up.do_dense = (sb == 0 && up.nbd > 0) ? 1 : 0;
+            if (p.d == 128) dkv_upper_kernel<128, 1, false><<<grid, 512, 0, s>>>(t, up);
+            else if (up.nbs - sb > 8) dkv_upper_kernel<64, 2, true><<<grid, 512, 0, s>>>(t, up);
+            else dkv_upper_kernel<64, 1, true><<<grid, 512, 0, s>>>(t, up);
+            GRP_TRY(hipGetLastError());
+        }
     }
-
-    // levels >= 2 (their own kernel, reductions and gathers, which share the two reduction buffers) beside level 1's kernel
-    const bool fork = side != s;
-    if (fork) {
-        GRP_TRY(hipEventRecord(ev_fork, s));
-        GRP_TRY(hipStreamWaitEvent(side, ev_fork, 0));
-    }
-    GroupArgs up = a;
-    up.lev_end = top + 1;
-    const dim3 grid((unsigned)(p.bh * (NR / G)));
-    const int per_launch = p.d == 64 ? 16 : 8;              // sparse blocks one launch covers
-    for (int sb = 0; sb == 0 || sb < up.nbs; sb += per_launch) {   // the first launch also takes the dense block (d = 64)
-        up.sparse_begin = sb;
-        up.do_dense = (sb == 0 && up.nbd > 0) ? 1 : 0;
-        if (p.d == 128) dkv_upper_kernel<128, 1, false><<<grid, 512, 0, side>>>(t, up);
-        else if (up.nbs - sb > 8) dkv_upper_kernel<64, 2, true><<<grid, 512, 0, side>>>(t, up);
-        else dkv_upper_kernel<64, 1, true><<<grid, 512, 0, side>>>(t, up);
-        GRP_TRY(hipGetLastError());
-    }
-    for (int l = top; l >= 2; --l) GRP_TRY(finish_level(p, t, up, l, groups[l], w, side));
-    if (fork) GRP_TRY(hipEventRecord(ev_join, side));
-
-    a.lev_end = 2;
+    a.lev_end = G ? 2 : top + 1;
     GRP_TRY(launch_group_kernel(p, t, a, s));
-    if (fork) GRP_TRY(hipStreamWaitEvent(s, ev_join, 0));           // `side` is in order: the lists are complete too
-    else if (lists) GRP_TRY(hipStreamWaitEvent(s, lists, 0));
-    return finish_level(p, t, a, 1, groups[1], w, s);     // level 1 has no reduction, so the buffers are free of a race
+    if (lists) GRP_TRY(hipStreamWaitEvent(s, lists, 0));
+    for (int l = top; l >= 1; --l) GRP_TRY(finish_level(p, t, a, l, groups[l], w, s));
+    return hipSuccess;
 }
 
 }  // namespace llsa

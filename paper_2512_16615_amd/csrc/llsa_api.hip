@@ -179,7 +179,7 @@ struct Aux {
     bool tried = false, ok = false;
     int device = -1;
     hipStream_t side = nullptr;
-    hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};   // start, lists ready, fork, join
+    hipEvent_t ev[2] = {nullptr, nullptr};   // fork (the side stream may start), lists ready (join)
 };
 
 struct llsa_plan_s {
@@ -200,7 +200,7 @@ static Aux *aux_for_call(const llsa_plan_s *plan, hipStream_t s) {
         a.tried = true;
         a.device = dev;
         bool ok = hipStreamCreateWithFlags(&a.side, hipStreamNonBlocking) == hipSuccess;
-        for (int i = 0; ok && i < 4; ++i) ok = hipEventCreateWithFlags(&a.ev[i], hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; ok && i < 2; ++i) ok = hipEventCreateWithFlags(&a.ev[i], hipEventDisableTiming) == hipSuccess;
         a.ok = ok;
     }
     return (a.ok && a.device == dev) ? &a : nullptr;
@@ -341,7 +341,12 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         StageScope sc(kBwdPre, call, s);
         LLSA_TRY(launch_bwd_pre(p, O, dO, D, s));
     }
-    {                                                       // Alg. 2 needs only the indices: beside dQ
+    // Alg. 2 needs only the indices, so it runs on the auxiliary stream beside kernels that do not read its
+    // lists.  Where the coarse levels use the grouped kernels (they write per-query-block partials, need no list,
+    // and a level above their range is dense and has none), that is behind dQ, in the shadow of those kernels:
+    // they are bound by LDS and leave wave slots and registers free, which dQ does not.  Otherwise it is beside dQ.
+    const bool shadow = aux && p.group;
+    auto transpose = [&]() -> llsa_status {
         const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
         if (aux) {
             LLSA_TRY(hipEventRecord(aux->ev[0], s));
@@ -350,25 +355,25 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         StageScope sc(kTranspose, call, side);              // bracketed on the stream it runs on
         LLSA_TRY(launch_csc(p, top_listed, indices, workspace, side));
         if (aux) LLSA_TRY(hipEventRecord(aux->ev[1], side));
-    }
+        return LLSA_OK;
+    };
+    if (!shadow) LLSA_TRY(transpose());
     LevelTable t = make_level_table(p, K, V, indices, workspace);
     {
         StageScope sc(kDq, call, s);
         if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, O, dO, LSE, D, dQ, s));
         else LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
     }
-    // The caller's stream waits for the key-major lists only where it first reads them: the grouped kernels
-    // write per-query-block partials and need no list, so they start right behind dQ.
+    if (shadow) LLSA_TRY(transpose());
+    // the caller's stream waits for the key-major lists where it first reads them (which also joins the streams)
     hipEvent_t lists = aux ? aux->ev[1] : nullptr;
-    const bool lists_late = lists && p.group && dkv_group_top(p) == p.Le;
-    if (lists && !lists_late) LLSA_TRY(hipStreamWaitEvent(s, lists, 0));
+    if (lists && !shadow) LLSA_TRY(hipStreamWaitEvent(s, lists, 0));
     // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
     {
         StageScope sc(kDkvCoarse, call, s);
         if (p.group) {                                      // levels above the grouped kernel's range first
             for (int l = p.Le; l > dkv_group_top(p); --l) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
-            LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, side, aux ? aux->ev[2] : nullptr,
-                                      aux ? aux->ev[3] : nullptr, lists_late ? lists : nullptr));
+            LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, shadow ? lists : nullptr));
         } else for (int l = p.Le; l >= 1; --l) {
             if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
             else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));

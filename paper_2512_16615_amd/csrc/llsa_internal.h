@@ -92,12 +92,10 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
                            const float *D, void *ws, void *dK, void *dV, hipStream_t s);
 int dkv_splits(const Plan &p, int l);    // workgroups sharing one key block's query list at level l
 // all coarse levels (dkv_group_top .. 1) at once, grouped by level-1 query block; fills the levels' fp32
-// gradients.  If `side` differs from `s`, the levels >= 2 run on `side` beside level 1's kernel: forked from
-// `s` through ev_fork and joined back through ev_join before level 1 adds their share.  `lists` (or null): event
-// after which the key-major lists are complete, recorded on `side`; `s` has waited for it when the call returns.
+// gradients.  `lists` (or null): event after which the key-major lists are complete, recorded on another stream;
+// `s` waits for it behind the kernels that need no list, before the gathers.
 hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
-                            const float *D, void *ws, hipStream_t s, hipStream_t side, hipEvent_t ev_fork,
-                            hipEvent_t ev_join, hipEvent_t lists);
+                            const float *D, void *ws, hipStream_t s, hipEvent_t lists);
 void dkv_group_sizes(const Plan &p, size_t *slab_bytes, size_t *red_bytes);
 int dkv_group_top(const Plan &p);         // highest level the grouped kernel takes (the rest: split kernel)
 
