@@ -1,7 +1,7 @@
-// Attention forward over the gathered lists on bf16 MFMA (B = 16, d = 64 or 128): Alg. 1's attention loop
+// Attention forward over the gathered lists on bf16 MFMA (B = 16, 32 or 64, d = 64 or 128): Alg. 1's attention loop
 // with Eq. 1-5 evaluated tile by tile with an online softmax.
 //
-// One wave owns one fine query block (16 queries).  Per tile of two 16-token key blocks it computes
+// One wave owns one tile of 16 queries.  Per tile of two 16-token key blocks it computes
 //   S^T = K Q^T   (A = key rows straight from global memory, B = the query block held in registers),
 // so every lane ends up with 4 keys x 1 query of S^T; the softmax statistics of a query are then a
 // reduction inside the lane plus two cross-row steps, and the probabilities already sit in the register

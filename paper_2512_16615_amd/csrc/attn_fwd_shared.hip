@@ -1,15 +1,15 @@
 // Attention forward over the gathered lists on bf16 MFMA, variant that shares the coarse levels
 // (B = 16, 32 or 64, d = 64 or 128, N a multiple of 256, at most 64 level-0 tiles of 16 tokens per list).
 //
-// The 16 fine query blocks under one level-1 query block use the same lists at every level >= 1 (Alg. 1,
-// enrichment loop: block i reads row i / B^l of I^(l)), i.e. the same coarse key/value tokens.  One
-// workgroup of 8 waves owns such a group; every wave owns two of its fine blocks.
+// 256 consecutive queries (B = 16: the 16 fine query blocks under one level-1 query block) use the same lists at
+// every level >= 1 (Alg. 1, enrichment loop: block i reads row i / B^l of I^(l)), i.e. the same coarse key/value
+// tokens.  One workgroup of 8 waves owns such a group; every wave owns one or two of its 16-query tiles.
 //   Phase A (levels >= 1): the workgroup stages each tile of two 16-token blocks (K and V rows) once in
 //     LDS, double-buffered; every wave reads the K operand once and multiplies it with both of its query
 //     blocks, likewise the transposed V operand, so the gather traffic of the coarse tokens is paid once
 //     per 256 queries instead of once per 16.
-//   Phase B (level 0): each wave walks the own K_0 blocks of each of its two query blocks, K rows straight
-//     from global memory into the A operand, V rows staged in a private LDS region.
+//   Phase B (level 0): each wave walks the level-0 tiles of each of its query tiles' lists; their K and V rows are
+//     fetched as whole cache lines and reach the operand layouts through the wave's private LDS tiles.
 // Score tiles are computed transposed (S^T = K Q^T) so that the accumulator layout (4 keys x 1 query per
 // lane) is the B operand of O^T += V^T P^T; see mfma_common.h for the register layouts.
 #include <type_traits>

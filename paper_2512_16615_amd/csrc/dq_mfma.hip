@@ -1,8 +1,8 @@
-// dQ of the gathered-list attention on bf16 MFMA (B = 16, d = 64 or 128), Sec. 4.3: query-major, the
+// dQ of the gathered-list attention on bf16 MFMA (B = 16, 32 or 64, d = 64 or 128), Sec. 4.3: query-major, the
 // same list walk as the forward, P recomputed from the saved logsumexp.
 // With P = exp(z - LSE), dP = dO V^T, dS = P o (dP - D), D = rowsum(dO o O):  dQ = scale dS K.
 //
-// One wave per fine query block.  Per tile of two 16-token key blocks:
+// One wave per tile of 16 queries.  Per tile of two 16-token key tiles:
 //   S^T = K Q^T, dP^T = V dO^T  (lane: 4 keys x 1 query)  ->  dS^T  ->  dQ^T += K^T dS^T.
 // K tiles are staged in the wave's LDS region and read twice (row-wise for S^T, transposed for dQ^T);
 // V rows go straight from global memory into the A operand.  The kernel also produces D for its 16

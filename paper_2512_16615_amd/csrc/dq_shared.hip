@@ -1,7 +1,7 @@
-// dQ on bf16 MFMA, variant that shares the coarse levels (B = 16, d = 64, N a multiple of 256); see
-// attn_fwd_shared.hip for the decomposition (a workgroup of 8 waves owns the 16 fine query blocks under one
-// level-1 query block, every wave two of them; the coarse key/value tiles are staged once per workgroup
-// in LDS, the level-0 blocks are walked per query block).
+// dQ on bf16 MFMA, variant that shares the coarse levels (B = 16, 32 or 64, d = 64 or 128, N a multiple of 256,
+// at most 64 level-0 tiles per list); see attn_fwd_shared.hip for the decomposition (a workgroup of 8 waves owns
+// 128 consecutive queries, which use the same lists at every level >= 1, every wave one 16-query tile; the coarse
+// key/value tiles are staged once per workgroup in LDS, the level-0 tiles are walked per query tile).
 // Per tile and query block:  S^T = K Q^T, dP^T = V dO^T  ->  dS^T = P^T o (dP^T - D)  ->  dQ^T += K^T dS^T,
 // with K read from LDS both row-wise (first product) and transposed (last product).
 // The kernel also produces D = rowsum(dO o O) for its queries and stores it for the key-major kernels.
