@@ -1,10 +1,11 @@
-// dK, dV of the gathered-list attention on bf16 MFMA (B = 16, d = 64 or 128), Sec. 4.3: key-major over
+// dK, dV of the gathered-list attention on bf16 MFMA (B = 16, 32 or 64, d = 64 or 128), Sec. 4.3: key-major over
 // the transposed lists of Alg. 2 (or over every query at the coarsest enriched level), with no mask and
 // no floating-point atomics.
 // With P = exp(z - LSE), dP = dO V^T, dS = P o (dP - D):  dK = scale dS^T Q,  dV = P^T dO.
 //
-// The queries that attend to a block of 16 level-l keys are the fine queries under the level-l query
-// blocks listed for it, walked in groups of 16 consecutive queries; a tile is two groups.  Per tile a wave
+// The unit of work is a tile of 16 level-l keys (a listed block of B keys is B / 16 tiles with one list).  The
+// queries that attend to it are the fine queries under the level-l query blocks listed for its block, walked in
+// groups of 16 consecutive queries; a tile of the loop is two groups.  Per tile a wave
 // computes
 //   S = Q K^T, dP = dO V^T   (lane: 4 queries x 1 key)  ->  P, dS  ->
 //   dV^T += dO^T P,  dK^T += Q^T dS   (A = the Q / dO tile read transposed from LDS, B = P / dS).
