@@ -1,5 +1,5 @@
 // Hierarchical Top-K selection, one level (Alg. 1, selection loop), fast path for bf16, B in {16, 32, 64} and
-// K <= 16: at most 256 candidates per query tile (select_fast_kernel) or any number (select_dense_kernel).
+// K <= 64: at most 256 candidates per query tile (select_fast_kernel) or any number (select_dense_kernel).
 //
 // One workgroup (256 threads) per level-l query block of 16 query tokens.  The candidate key rows (all
 // n_L tokens at the coarsest level, the 16 * K_l children of the parent's picks below it) and the 16
@@ -19,8 +19,8 @@ __device__ __forceinline__ void unpack8(u32x4 w, float *f) {
     }
 }
 
-// MC = candidates per lane (8: up to 128 candidates, 16: up to 256)
-template <int D, int MC>
+// MC = candidates per lane (8: up to 128 candidates, 16: up to 256); KW = winners per lane (K <= 16 KW)
+template <int D, int MC, int KW>
 __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
                                                            int64_t n_l, const int32_t *__restrict__ parent, int Kp,
                                                            int Kout, int32_t *__restrict__ out, int C, int64_t nblk,
@@ -73,7 +73,9 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
         if (cg + 16 * m >= C) sc[m] = -INFINITY;
 
     // K rounds of arg-max over the row's candidates (score descending, position ascending)
-    int mine = 0;                                           // lane k of the row group keeps the k-th winner
+    int mine[KW];                                           // lane k % 16 of the row group keeps the k-th winner
+#pragma unroll
+    for (int w = 0; w < KW; ++w) mine[w] = 0;
     for (int k = 0; k < Kout; ++k) {
         float bs = sc[0];
         int bp = cg;
@@ -89,16 +91,28 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
 #pragma unroll
         for (int m = 0; m < MC; ++m)
             if (bp == cg + 16 * m) sc[m] = -INFINITY;
-        if (cg == k) mine = bp;
+#pragma unroll
+        for (int w = 0; w < KW; ++w)
+            if (k == cg + 16 * w) mine[w] = bp;
     }
     // candidate positions ascend with key id (parent rows are ascending): rank the winners by position
-    int rank = 0;
-    for (int k = 0; k < Kout; ++k) rank += (__shfl(mine, k, 16) < mine) ? 1 : 0;
+    int rank[KW];
+#pragma unroll
+    for (int w = 0; w < KW; ++w) rank[w] = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < KW; ++w2)
+        for (int k = 0; k < 16 && 16 * w2 + k < Kout; ++k) {
+            const int other = __shfl(mine[w2], k, 16);
+#pragma unroll
+            for (int w = 0; w < KW; ++w) rank[w] += (other < mine[w]) ? 1 : 0;
+        }
     const int64_t i = r * 16 + row;
-    if (cg < Kout && i < n_l) {
-        const int64_t id = prow ? ((int64_t)prow[mine >> lb] << lb) + (mine & Bm1) : mine;
-        out[(bh * n_l + i) * Kout + rank] = (int32_t)id;
-    }
+#pragma unroll
+    for (int w = 0; w < KW; ++w)
+        if (cg + 16 * w < Kout && i < n_l) {
+            const int64_t id = prow ? ((int64_t)prow[mine[w] >> lb] << lb) + (mine[w] & Bm1) : mine[w];
+            out[(bh * n_l + i) * Kout + rank[w]] = (int32_t)id;
+        }
 }
 
 // More than 256 candidates: a coarsest level of more than 256 tokens (few levels for the sequence length, or the
@@ -107,7 +121,7 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
 // keeps its K best so far (lane k: the k-th best), which compete in the next chunk's rounds as one more candidate
 // per lane.  Their key ids are lower than the chunk's (candidate positions ascend with the key id), so the tie
 // rule holds.
-template <int D>
+template <int D, int KW>
 __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
                                                             int64_t n_l, const int32_t *__restrict__ parent, int Kp, int C,
                                                             int Kout, int32_t *__restrict__ out, int64_t nblk, int lb) {
@@ -129,8 +143,10 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
     }
     const int cg = tid & 15, row = tid >> 4;
     constexpr int kNone = 0x7fffffff;
-    float best_s = -INFINITY;                               // lane k of the row group: k-th best so far and its key id
-    int best_id = kNone;
+    float best_s[KW];                                       // lane k % 16 of the row group: k-th best so far and its key id
+    int best_id[KW];
+#pragma unroll
+    for (int w = 0; w < KW; ++w) { best_s[w] = -INFINITY; best_id[w] = kNone; }
     for (int c0 = 0; c0 < C; c0 += 256) {
         __syncthreads();                                    // the previous chunk has been scored
         for (int c = tid; c < 256 * CH; c += 256) {
@@ -161,40 +177,59 @@ __global__ void __launch_bounds__(256) select_dense_kernel(const uint16_t *__res
             if (pos0 + 16 * m >= C) sc[m] = -INFINITY;
         }
 
-        float old_s = best_s, new_s = -INFINITY;            // this lane's entry of the running list competes too
-        int old_id = best_id, new_id = kNone;
+        float old_s[KW], new_s[KW];                         // this lane's entries of the running list compete too
+        int old_id[KW], new_id[KW];
+#pragma unroll
+        for (int w = 0; w < KW; ++w) { old_s[w] = best_s[w]; old_id[w] = best_id[w]; new_s[w] = -INFINITY; new_id[w] = kNone; }
         for (int k = 0; k < Kout; ++k) {
-            float bs = old_s;
-            int bp = old_id;
+            float bs = old_s[0];
+            int bp = old_id[0];
+#pragma unroll
+            for (int w = 1; w < KW; ++w)                          // the running entries are in no id order
+                if (old_s[w] > bs || (old_s[w] == bs && old_id[w] < bp)) { bs = old_s[w]; bp = old_id[w]; }
 #pragma unroll
             for (int m = 0; m < MC; ++m)
-                if (sc[m] > bs) { bs = sc[m]; bp = id[m]; }      // ascending ids: strict '>' keeps the lowest
+                if (sc[m] > bs) { bs = sc[m]; bp = id[m]; }      // ids above the running ones, ascending: strict '>'
 #pragma unroll
             for (int o = 8; o >= 1; o >>= 1) {
                 const float os = __shfl_xor(bs, o, 16);
                 const int op = __shfl_xor(bp, o, 16);
                 if (os > bs || (os == bs && op < bp)) { bs = os; bp = op; }
             }
-            if (bp == old_id) { old_s = -INFINITY; old_id = kNone; }
+#pragma unroll
+            for (int w = 0; w < KW; ++w)
+                if (bp == old_id[w]) { old_s[w] = -INFINITY; old_id[w] = kNone; }
 #pragma unroll
             for (int m = 0; m < MC; ++m)
                 if (bp == id[m]) sc[m] = -INFINITY;
-            if (cg == k) { new_s = bs; new_id = bp; }
+#pragma unroll
+            for (int w = 0; w < KW; ++w)
+                if (k == cg + 16 * w) { new_s[w] = bs; new_id[w] = bp; }
         }
-        best_s = new_s;
-        best_id = new_id;
+#pragma unroll
+        for (int w = 0; w < KW; ++w) { best_s[w] = new_s[w]; best_id[w] = new_id[w]; }
     }
-    int rank = 0;                                           // rows are written in ascending id order
-    for (int k = 0; k < Kout; ++k) rank += (__shfl(best_id, k, 16) < best_id) ? 1 : 0;
+    int rank[KW];                                           // rows are written in ascending id order
+#pragma unroll
+    for (int w = 0; w < KW; ++w) rank[w] = 0;
+#pragma unroll
+    for (int w2 = 0; w2 < KW; ++w2)
+        for (int k = 0; k < 16 && 16 * w2 + k < Kout; ++k) {
+            const int other = __shfl(best_id[w2], k, 16);
+#pragma unroll
+            for (int w = 0; w < KW; ++w) rank[w] += (other < best_id[w]) ? 1 : 0;
+        }
     const int64_t i = r * 16 + row;
-    if (cg < Kout && i < n_l) out[(bh * n_l + i) * Kout + rank] = best_id;
+#pragma unroll
+    for (int w = 0; w < KW; ++w)
+        if (cg + 16 * w < Kout && i < n_l) out[(bh * n_l + i) * Kout + rank[w]] = best_id[w];
 }
 
 // true if the fast kernel covers this level
 bool select_fast_ok(const Plan &p, int l) {
     const int64_t C = (l == p.L) ? p.n[l] : (int64_t)p.Kl[l] * p.B;
     // any number of candidates (256 at a time beyond 256); 16 consecutive query tokens share their candidates
-    return p.fast && p.Kl[l - 1] <= 16 && p.n[l] < ((int64_t)1 << 30) && C < (1 << 30) &&
+    return p.fast && p.Kl[l - 1] <= 64 && p.n[l] < ((int64_t)1 << 30) && C < (1 << 30) &&
            (l == p.L || p.n[l] % 16 == 0);
 }
 
@@ -207,18 +242,25 @@ hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_
     const int Kp = top ? 0 : p.Kl[l], Kout = p.Kl[l - 1];
     dim3 grid((unsigned)(p.bh * nblk));
     const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
+    const bool wide = Kout > 16;                            // up to 4 winners per lane instead of one
+#define LLSA_SEL(kernel, ...) kernel<<<grid, 256, 0, s>>>(__VA_ARGS__)
     if (C > 256) {
-        if (p.d == 64) select_dense_kernel<64><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
-        else select_dense_kernel<128><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
+        if (p.d == 64 && !wide) LLSA_SEL((select_dense_kernel<64, 1>), Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
+        else if (p.d == 64) LLSA_SEL((select_dense_kernel<64, 4>), Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
+        else if (!wide) LLSA_SEL((select_dense_kernel<128, 1>), Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
+        else LLSA_SEL((select_dense_kernel<128, 4>), Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
         return hipGetLastError();
     }
     if (p.d == 64) {
-        if (C <= 128) select_fast_kernel<64, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
-        else select_fast_kernel<64, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<64, 8, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        else if (!wide) LLSA_SEL((select_fast_kernel<64, 16, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        else LLSA_SEL((select_fast_kernel<64, 16, 4>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
     } else {
-        if (C <= 128) select_fast_kernel<128, 8><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
-        else select_fast_kernel<128, 16><<<grid, 256, 0, s>>>(Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<128, 8, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        else if (!wide) LLSA_SEL((select_fast_kernel<128, 16, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        else LLSA_SEL((select_fast_kernel<128, 16, 4>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
     }
+#undef LLSA_SEL
     return hipGetLastError();
 }
 

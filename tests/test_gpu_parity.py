@@ -96,7 +96,7 @@ def test_config1_n4096_bf16_all_heads():
     dict(name="dense_top_272_L2", batch=1, heads=1, d=64, N=69632, B=16, K=4, L=2, dtype="bf16", kind="gaussian"),
     # blocks of 64 tokens (four 16-token tiles) on the MFMA kernels: one-token top; 512 candidates per selection row
     # (two chunks) and 32 level-0 tiles per list; 64 level-0 tiles (one query tile per wave); 128 level-0 tiles and
-    # K = 32 (per-wave kernels, portable selection); no enrichment; d = 128
+    # K = 32 (per-wave kernels); no enrichment; d = 128
     dict(name="B64_small", batch=1, heads=2, d=64, N=4096, B=64, K=2, L=2, dtype="bf16", kind="smooth"),
     dict(name="B64_K8", batch=1, heads=1, d=64, N=65536, B=64, K=8, L=2, dtype="bf16", kind="smooth"),
     dict(name="B64_K16", batch=1, heads=2, d=64, N=16384, B=64, K=16, L=2, dtype="bf16", kind="gaussian"),
@@ -107,9 +107,19 @@ def test_config1_n4096_bf16_all_heads():
     # with a ragged dense level of 66 tokens
     dict(name="B32_L3", batch=1, heads=2, d=64, N=32768, B=32, K=4, L=3, dtype="bf16", kind="gaussian"),
     dict(name="B32_ragged", batch=1, heads=2, d=64, N=2112, B=32, K=8, L=1, dtype="bf16", kind="gaussian"),
+    # more than 16 winners per selection row (up to 4 per lane): 20 of 64 at the top, 20 of 320 (two chunks) below
+    dict(name="K20", batch=1, heads=2, d=64, N=16384, B=16, K=20, L=2, dtype="bf16", kind="smooth"),
 ])
 def test_edge_shapes(cfg):
     _full_parity(cfg, 0x5EED0 + len(cfg["name"]))
+
+
+def test_portable_kernels_on_a_fast_path_shape():
+    """desc.kernel_path = 1 forces the scalar kernels on a shape the MFMA kernels would take: same bars."""
+    cfg = dict(name="portable", batch=1, heads=2, d=64, N=4096, B=16, K=8, L=2, dtype="bf16", kind="smooth")
+    _full_parity(cfg, 0x5EED77, plan_kw=dict(kernel_path=1))
+    cfg = dict(name="portable_B64", batch=1, heads=1, d=64, N=4096, B=64, K=2, L=1, dtype="bf16", kind="gaussian")
+    _full_parity(cfg, 0x5EED78, plan_kw=dict(kernel_path=1))
 
 
 def test_dense_limit_on_gpu():

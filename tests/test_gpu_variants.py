@@ -1,7 +1,7 @@
 """GPU parity on the shapes of the paper's scaling and ablation studies (Fig. 4, Table 5), beyond the benchmark's five
 configurations: longer sequences at the d = 64 head geometry, the paper's own choice of the number of levels
 (L = 2 at 256 x 256), a single coarse level (L = 1, the prior single-level Top-K design), partial enrichment
-(L_e < L), larger K, and a block size other than 16 (portable kernels).  Same bars as the other parity tests.
+(L_e < L), larger K, and the paper's other block size, 64.  Same bars as the other parity tests.
 """
 import pytest
 
@@ -60,7 +60,7 @@ def test_n1048576_K16_two_upper_launches():
     _run(cfg, 0x115A2070, heads=[(0, 0)], n_row_chunks=2)
 
 
-def test_block_size_64_portable_kernels():
+def test_block_size_64():
     """B = 64 (the larger block of the paper's efficiency comparison): N = 16384 -> 256 -> 4 tokens, L = 2."""
     cfg = dict(BASE, name="n16384_B64", N=16384, heads=2, B=64, K=4, L=2)
     _run(cfg, 0x115A2050, heads=[(0, 1)], n_row_chunks=3, full_backward_head=(0, 1))
