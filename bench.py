@@ -183,7 +183,7 @@ def sweep_cases(which):
         for N in (4096, 16384, 65536, 262144, 1048576):
             add("n", N, deepest[N])
     if which in ("L", "all"):
-        for N, Ls in ((65536, (1, 2, 3)), (262144, (2, 3, 4))):
+        for N, Ls in ((65536, (1, 2, 3)), (262144, (1, 2, 3, 4))):
             for L in Ls:
                 add("L", N, L)
     if which in ("Le", "all"):

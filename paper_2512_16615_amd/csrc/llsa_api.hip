@@ -79,10 +79,15 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
         off += (size_t)p.bh * p.n[l + 1] * p.Kl[l] * sizeof(int32_t);
     }
     p.idx_bytes = off;
-    // selection holds one row of candidate scores per wave in LDS
-    if (p.n[p.L] > kMaxCand) return LLSA_ERR_UNSUPPORTED;
-    for (int l = 1; l < p.L; ++l)
-        if ((int64_t)p.Kl[l] * p.B > kMaxCand) return LLSA_ERR_UNSUPPORTED;
+    // MFMA kernels: bf16, blocks of 1, 2 or 4 16-token tiles, d = 64 / 128, and whole workgroups of 4 query tiles per head
+    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && (d.B == 16 || d.B == 32 || d.B == 64) &&
+             (d.d == 64 || d.d == 128) && d.N % 64 == 0;
+    p.lb = !p.fast ? 0 : d.B == 16 ? 4 : d.B == 32 ? 5 : 6;
+    // the portable selection holds one row of candidate scores per wave in LDS (the fast one takes any number)
+    for (int l = 1; l <= p.L; ++l) {
+        const int64_t cand = (l == p.L) ? p.n[l] : (int64_t)p.Kl[l] * p.B;
+        if (cand > kMaxCand && !select_fast_ok(p, l)) return LLSA_ERR_UNSUPPORTED;
+    }
     int64_t m = 0;
     for (int l = 0; l <= p.Le; ++l) m += (l < p.L) ? (int64_t)p.Kl[l] * p.B : p.n[l];
     p.list_len = (int)m;
@@ -109,10 +114,6 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
         p.dKacc_off[l] = ws; ws = align_up(ws + bytes);
         p.dVacc_off[l] = ws; ws = align_up(ws + bytes);
     }
-    // MFMA kernels: bf16, blocks of 1, 2 or 4 16-token tiles, d = 64 / 128, and whole workgroups of 4 query tiles per head
-    p.fast = d.kernel_path == 0 && d.dtype == LLSA_BF16 && (d.B == 16 || d.B == 32 || d.B == 64) &&
-             (d.d == 64 || d.d == 128) && d.N % 64 == 0;
-    p.lb = !p.fast ? 0 : d.B == 16 ? 4 : d.B == 32 ? 5 : 6;
     // coarse-level dK/dV grouped by level-1 query block: d = 64, whole groups of 256 queries, short lists
     int coarse_blocks = 0;
     for (int l = 1; l <= dkv_group_top(p); ++l) coarse_blocks += (l < p.L) ? p.Kl[l] : (int)((p.n[l] + 15) / 16);

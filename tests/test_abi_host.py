@@ -60,6 +60,7 @@ def test_plan_partial_top_level(llsa):
     (dict(dtype=7), 3),
     (dict(B=128), 3),
     (dict(L=1), 3),                    # 4096 coarse tokens: fine;  see below
+    (dict(N=262144, L=1, kernel_path=1), 3),   # 16384 candidates per row: beyond the portable selection's LDS row
 ])
 def test_plan_rejects_bad_problems(llsa, kw, status):
     args = dict(batch=1, heads=16, N=65536, d=64, B=16, K=8, L=3, Le=None)
@@ -70,6 +71,9 @@ def test_plan_rejects_bad_problems(llsa, kw, status):
     with pytest.raises(llsa.LlsaError) as e:
         llsa.Plan(**args)
     assert f"status {status}" in str(e.value)
+    if "kernel_path" in kw:             # the chunked selection of the MFMA path takes any number of candidates
+        del args["kernel_path"]
+        llsa.Plan(**args)
 
 
 def test_null_pointers_are_refused_before_any_launch(llsa):

@@ -47,6 +47,14 @@ def test_n262144_d64_L4():
 
 
 @pytest.mark.timeout(600)
+def test_n262144_single_level():
+    """The single-level method at 512 x 512 tokens: 16384 coarse tokens, every one a selection candidate and a key of
+    the dense level (the quadratic regime the paper's hierarchy removes)."""
+    cfg = dict(BASE, name="n262144_L1", N=262144, heads=1, L=1)
+    _run(cfg, 0x115A2035, heads=[(0, 0)], n_row_chunks=1)
+
+
+@pytest.mark.timeout(600)
 def test_n1048576_d64_L4():
     """1024 x 1024 pixel tokens, one head: 16^5 tokens, L = 4, coarsest level of 16 tokens."""
     cfg = dict(BASE, name="n1048576_d64", N=1048576, heads=1, L=4)
