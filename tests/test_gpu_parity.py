@@ -107,6 +107,11 @@ def test_config1_n4096_bf16_all_heads():
     # with a ragged dense level of 66 tokens
     dict(name="B32_L3", batch=1, heads=2, d=64, N=32768, B=32, K=4, L=3, dtype="bf16", kind="gaussian"),
     dict(name="B32_ragged", batch=1, heads=2, d=64, N=2112, B=32, K=8, L=1, dtype="bf16", kind="gaussian"),
+    # no reweighting and an explicit scale on the MFMA kernels (grouped and per-level dK/dV)
+    dict(name="noweight_bf16", batch=1, heads=2, d=64, N=4096, B=16, K=8, L=2, reweight=0, sm_scale=0.2, dtype="bf16",
+         kind="gaussian"),
+    dict(name="noweight_B32", batch=1, heads=1, d=128, N=4096, B=32, K=4, L=2, reweight=0, sm_scale=0.05, dtype="bf16",
+         kind="gaussian"),
     # more than 16 winners per selection row (up to 4 per lane): 20 of 64 at the top, 20 of 320 (two chunks) below
     dict(name="K20", batch=1, heads=2, d=64, N=16384, B=16, K=20, L=2, dtype="bf16", kind="smooth"),
 ])
