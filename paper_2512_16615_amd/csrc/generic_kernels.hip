@@ -364,9 +364,13 @@ __global__ void csc_count_kernel(CscLevels a) {
     const int64_t bh = e / L.eph;
     atomicAdd(&L.cnt[bh * L.T + L.I[e]], 1);
 }
-// one workgroup per (head, level): C = exclusive scan of cnt (T+1 entries), cnt reset to 0 for the fill pass
-__global__ void __launch_bounds__(1024) csc_scan_kernel(CscLevels a) {
-    __shared__ int32_t wsum[16];
+// one workgroup per (head, level): C = exclusive scan of cnt (T+1 entries), cnt reset to 0 for the fill pass.
+// 256 threads, so that a workgroup finds room on a CU beside the LDS-bound dK/dV kernels it runs in the shadow of
+// (with 1024 threads it waited for a whole CU to drain).
+constexpr int kScanThreads = 256;
+__global__ void __launch_bounds__(kScanThreads) csc_scan_kernel(CscLevels a) {
+    constexpr int NW = kScanThreads / 64;
+    __shared__ int32_t wsum[NW];
     __shared__ int32_t carry;
     const CscLevel &L = a.lv[blockIdx.y];
     const int64_t bh = blockIdx.x, T = L.T;
@@ -374,12 +378,15 @@ __global__ void __launch_bounds__(1024) csc_scan_kernel(CscLevels a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x == 0) carry = 0;
     __syncthreads();
-    for (int64_t base = 0; base < T; base += 1024) {
-        const int64_t i = base + threadIdx.x;
-        const int32_t v = i < T ? cn[i] : 0;
-        int32_t x = v;                                     // inclusive scan inside the wave
+    for (int64_t base = 0; base < T; base += 4 * kScanThreads) {
+        // four consecutive keys per thread
+        const int64_t i0 = base + 4 * threadIdx.x;
+        int32_t v[4], x = 0;
 #pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
+        for (int k = 0; k < 4; ++k) { v[k] = i0 + k < T ? cn[i0 + k] : 0; x += v[k]; }
+        const int32_t mine = x;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {                  // inclusive scan of the threads' sums inside the wave
             const int32_t y = __shfl_up(x, o, 64);
             if (lane >= o) x += y;
         }
@@ -387,9 +394,14 @@ __global__ void __launch_bounds__(1024) csc_scan_kernel(CscLevels a) {
         __syncthreads();
         int32_t pre = carry;
         for (int w2 = 0; w2 < wave; ++w2) pre += wsum[w2];
-        if (i < T) { Co[i] = pre + x - v; cn[i] = 0; }
+        int32_t run = pre + x - mine;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (i0 + k < T) { Co[i0 + k] = run; cn[i0 + k] = 0; }
+            run += v[k];
+        }
         __syncthreads();
-        if (threadIdx.x == 1023) carry = pre + x;
+        if (threadIdx.x == kScanThreads - 1) carry = pre + x;
         __syncthreads();
     }
     if (threadIdx.x == 0) Co[T] = carry;
@@ -441,7 +453,7 @@ hipError_t launch_csc(const Plan &p, int top, const int32_t *indices, void *ws, 
     const unsigned nl = (unsigned)(top + 1);
     csc_zero_kernel<<<dim3((unsigned)((max_nk + 255) / 256), nl), 256, 0, s>>>(a);
     csc_count_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
-    csc_scan_kernel<<<dim3(p.bh, nl), 1024, 0, s>>>(a);
+    csc_scan_kernel<<<dim3(p.bh, nl), kScanThreads, 0, s>>>(a);
     csc_fill_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
     csc_sort_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
     return hipGetLastError();
