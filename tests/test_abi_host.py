@@ -44,6 +44,20 @@ def test_plan_level_table_headline(llsa):
         assert p.pyramid_info(x, 1)[0] == 4096 and p.pyramid_info(x, 3)[0] == 16
 
 
+def test_plan_other_block_sizes_and_wide_lists(llsa):
+    p = llsa.Plan(1, 16, 65536, 64, 64, 8, 2)           # B = 64: 65536 -> 1024 -> 16
+    assert [(li.rows, li.K_l) for li in p.levels] == [(1024, 8), (16, 8)]
+    pooled = 3 * 16 * (1024 + 16) * 64 * 2
+    assert pooled <= p.workspace_bytes(False) <= pooled + 6 * 256
+    p = llsa.Plan(1, 2, 32768, 64, 32, 4, 3)            # B = 32: 32768 -> 1024 -> 32 -> 1
+    assert [(li.rows, li.K_l) for li in p.levels] == [(1024, 4), (32, 4), (1, 1)]
+    p = llsa.Plan(1, 2, 65536, 64, 16, 64, 3)           # K = 64: capped by the rows of the level above
+    assert [(li.rows, li.K_l) for li in p.levels] == [(4096, 64), (256, 64), (16, 16)]
+    assert p.indices_bytes() == 2 * (4096 * 64 + 256 * 64 + 16 * 16) * 4
+    with pytest.raises(llsa.LlsaError):
+        llsa.Plan(1, 2, 65536, 64, 16, 65, 3)           # K beyond 64
+
+
 def test_plan_partial_top_level(llsa):
     p = llsa.Plan(2, 16, 16384, 64, 16, 8, 3)          # top level holds 4 tokens: K_2 = 4
     assert [(li.rows, li.K_l) for li in p.levels] == [(1024, 8), (64, 8), (4, 4)]
