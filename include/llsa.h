@@ -38,7 +38,7 @@ typedef enum {
     LLSA_ERR_NULL = 1,        /* a required pointer is NULL                              */
     LLSA_ERR_BAD_SHAPE = 2,   /* N not divisible by B^L, L < 1, Le outside 0..L, K < 1...*/
     LLSA_ERR_UNSUPPORTED = 3, /* a (d, B, K, dtype, size) combination no kernel handles  */
-    LLSA_ERR_WORKSPACE = 4,   /* reserved                                                */
+    LLSA_ERR_WORKSPACE = 4,   /* llsa_forward_static: the plan needs more than the static workspace */
     LLSA_ERR_RUNTIME = 5      /* a HIP launch failed                                     */
 } llsa_status;
 
@@ -126,6 +126,26 @@ llsa_status llsa_forward(const llsa_plan_t *plan, const void *Q, const void *K, 
 llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, const void *O,
                           const float *LSE, const int32_t *indices, const void *dO, void *dQ, void *dK,
                           void *dV, void *workspace, void *hip_stream);
+
+/*
+ * llsa_forward for callers that cannot allocate device memory or have none to pass: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, kernels and results as
+ * llsa_forward, except that the workspace (the pooled levels of Q, K, V) is a static device array inside the
+ * library, LLSA_STATIC_WORKSPACE_BYTES on every GPU the library is used on, held until the process ends.
+ * The call allocates and frees nothing.
+ *   - LLSA_ERR_WORKSPACE if llsa_plan_workspace_bytes(plan, 0) > llsa_static_workspace_bytes(): checked on
+ *     the host first, nothing is enqueued (the headline shape, 16 heads of 65536 tokens at d = 64, needs 25.6 MiB).
+ *   - The first call on a device looks the array's address up on that device (hipGetSymbolAddress); make
+ *     that call outside stream capture.
+ *   - Every call on one GPU uses the same array: calls that overlap on a GPU (two streams, two host threads)
+ *     race.  The array keeps the last call's pooled levels; nothing in it needs clearing, since a call writes
+ *     every byte it reads.  llsa_backward cannot use it: set desc.bwd_repool = 1 and pass backward a
+ *     workspace of its own.
+ */
+#define LLSA_STATIC_WORKSPACE_BYTES (32u << 20)
+size_t llsa_static_workspace_bytes(void);
+llsa_status llsa_forward_static(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O,
+                                float *LSE, int32_t *indices, void *hip_stream);
 
 /* ---- the steps of the path one by one (same kernels; used for step-wise parity checks) ---- */
 

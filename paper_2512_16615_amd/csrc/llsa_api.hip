@@ -207,6 +207,31 @@ static Aux *aux_for_call(const llsa_plan_s *plan, hipStream_t s) {
     return (a.ok && a.device == dev) ? &a : nullptr;
 }
 
+// ---- forward pass for callers that cannot allocate: the workspace is a static device array ----
+// One copy of the array exists on every GPU the library's code object is loaded on, at an address of its own;
+// in host code the array's name is only a handle for hipGetSymbolAddress, never a device address.
+constexpr size_t kStaticWorkspaceBytes = (size_t)LLSA_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticWorkspaceBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mu;
+static void *g_scratch_ptr[kMaxDevices];     // device address of `scratch` on device i, once looked up there
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+static llsa_status static_workspace(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return LLSA_ERR_RUNTIME;
+    if (dev < 0 || dev >= kMaxDevices) return LLSA_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return LLSA_ERR_RUNTIME;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LLSA_OK;
+}
+
 extern "C" {
 
 llsa_status llsa_plan(const llsa_desc *desc, llsa_plan_t **out) {
@@ -311,6 +336,19 @@ llsa_status llsa_forward(const llsa_plan_t *plan, const void *Q, const void *K, 
     }
     StageScope sc(kAttnFwd, call, s);
     return llsa_attention(plan, Q, K, V, indices, workspace, O, LSE, hip_stream);
+}
+
+// ---- forward pass for callers that cannot allocate (workspace: the static device array above) ----
+size_t llsa_static_workspace_bytes(void) { return kStaticWorkspaceBytes; }
+
+llsa_status llsa_forward_static(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O,
+                                float *LSE, int32_t *indices, void *hip_stream) {
+    if (!plan || !Q || !K || !V || !O || !LSE || !indices) return LLSA_ERR_NULL;
+    if (plan->p.ws_fwd > kStaticWorkspaceBytes) return LLSA_ERR_WORKSPACE;     // host-side, before any HIP call
+    void *ws = nullptr;
+    const llsa_status st = static_workspace(&ws);
+    if (st != LLSA_OK) return st;
+    return llsa_forward(plan, Q, K, V, O, LSE, indices, ws, hip_stream);
 }
 
 llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices, void *workspace, void *hip_stream) {
@@ -454,7 +492,7 @@ const char *llsa_status_string(llsa_status s) {
         case LLSA_ERR_NULL: return "null pointer";
         case LLSA_ERR_BAD_SHAPE: return "bad shape (N must be divisible by B^L; L >= 1; 0 <= Le <= L; K >= 1)";
         case LLSA_ERR_UNSUPPORTED: return "unsupported d / B / K / dtype / size";
-        case LLSA_ERR_WORKSPACE: return "workspace error";
+        case LLSA_ERR_WORKSPACE: return "the problem's forward workspace exceeds the library's static one";
         case LLSA_ERR_RUNTIME: return "HIP launch failed";
     }
     return "unknown status";

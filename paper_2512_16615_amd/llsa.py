@@ -33,7 +33,8 @@ class _Desc(ctypes.Structure):
 EXPORTS = ["llsa_plan", "llsa_plan_destroy", "llsa_plan_workspace_bytes", "llsa_plan_indices_bytes",
            "llsa_plan_level_info", "llsa_plan_pyramid_info", "llsa_plan_csc_info", "llsa_forward", "llsa_backward",
            "llsa_pool", "llsa_select_level", "llsa_attention", "llsa_index_transpose", "llsa_reorder", "llsa_status_string",
-           "llsa_stage_count", "llsa_stage_name", "llsa_stage_timing_begin", "llsa_stage_timing_end"]
+           "llsa_stage_count", "llsa_stage_name", "llsa_stage_timing_begin", "llsa_stage_timing_end",
+           "llsa_static_workspace_bytes", "llsa_forward_static"]
 
 
 def load():
@@ -61,6 +62,10 @@ def load():
     lib.llsa_plan_csc_info.restype = i32
     lib.llsa_forward.argtypes = [vp] * 9
     lib.llsa_forward.restype = ctypes.c_int
+    lib.llsa_forward_static.argtypes = [vp] * 8
+    lib.llsa_forward_static.restype = ctypes.c_int
+    lib.llsa_static_workspace_bytes.argtypes = []
+    lib.llsa_static_workspace_bytes.restype = sz
     lib.llsa_backward.argtypes = [vp] * 13
     lib.llsa_backward.restype = ctypes.c_int
     lib.llsa_pool.argtypes = [vp] * 6
@@ -201,6 +206,21 @@ def forward(p: Plan, Q, K, V, O=None, LSE=None, indices=None, workspace=None):
     _check(load().llsa_forward(p._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(indices), _ptr(workspace),
                                _stream()), "llsa_forward")
     return O, LSE, indices, workspace
+
+
+def forward_static(p: Plan, Q, K, V, O, LSE, indices):
+    """``llsa_forward_static``: forward pass on the library's static workspace; the caller passes every
+    output buffer, and neither the binding nor the library allocates."""
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (O, "O")):
+        _chk_tensor(p, t, n)
+    if indices.numel() * 4 < p.indices_bytes() or LSE.numel() < p.batch * p.heads * p.N:
+        raise LlsaError("indices or LSE buffer too small")
+    _check(load().llsa_forward_static(p._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(indices), _stream()),
+           "llsa_forward_static")
+
+
+def static_workspace_bytes() -> int:
+    return load().llsa_static_workspace_bytes()
 
 
 def backward(p: Plan, Q, K, V, O, LSE, indices, dO, workspace, dQ=None, dK=None, dV=None):

@@ -121,3 +121,16 @@ def test_reorder_validates_on_the_host(llsa):
     assert lib.llsa_reorder(1, 4096, 4, llsa.BF16, 0, a, b, None) == 2      # 8-byte rows
     assert lib.llsa_reorder(1, 4096, 64, 9, 0, a, b, None) == 3             # unknown dtype
     assert lib.llsa_reorder(1, 4096, 64, llsa.BF16, 0, a, ctypes.c_void_p(4096 + 128), None) == 2   # overlap
+
+
+def test_forward_static_checks_the_size_on_the_host(llsa):
+    """llsa_forward_static refuses NULL and a plan beyond the static workspace before any HIP call."""
+    lib = llsa.load()
+    assert lib.llsa_static_workspace_bytes() == 32 << 20
+    big = llsa.Plan(1, 8, 262144, 128, 16, 16, 4)                 # pooled levels: about 102 MiB
+    assert big.workspace_bytes(False) > lib.llsa_static_workspace_bytes()
+    a = ctypes.c_void_p(4096)                                      # never dereferenced
+    assert lib.llsa_forward_static(big._h, a, a, a, a, a, a, None) == 4
+    assert lib.llsa_forward_static(big._h, a, a, None, a, a, a, None) == 1
+    headline = llsa.Plan(1, 16, 65536, 64, 16, 8, 3)
+    assert headline.workspace_bytes(False) <= lib.llsa_static_workspace_bytes()
