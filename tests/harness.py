@@ -5,10 +5,11 @@ Tolerances (written here once, used by every parity test):
   * selection indices: bit-exact, level by level with teacher forcing (the oracle's level-l selection is fed the
     GPU's own parent lists); a row may differ only where the gap between the K-th and (K+1)-th fp64 score is
     below 1e-5 relative;
-  * O, dQ, dK, dV: max-abs error <= 2e-2 (bf16 I/O) or 1e-4 (fp32 I/O), where for bf16 outputs of magnitude
-    above 1 the bound scales with the magnitude (half an ulp of bf16 is 2^-9 relative, so a bf16 result cannot
-    be closer than that to the fp64 value): |err| <= tol * max(1, |ref|);
-  * LSE (always fp32): 1e-4 (fp32 I/O) or 1e-3 (bf16 I/O).
+  * O, dQ, dK, dV: plain max-abs error <= 2e-2 (bf16 I/O) or 1e-4 (fp32 I/O), as stated for this build; no
+    scaling with the magnitude of the value.  (check_close can add a term `ulp * |ref|`; every parity test passes
+    ulp = 0.)  Every comparison records the max-abs error, the largest |ref| and the number of elements above the
+    bound (`STATS`, written to gpurun_out/parity_stats.json at the end of a GPU test session);
+  * LSE (always fp32): plain 1e-4 (fp32 I/O) or 1e-3 (bf16 I/O).
 """
 from __future__ import annotations
 
@@ -21,7 +22,9 @@ import torch
 from oracle import llsa_oracle as orc
 from paper_2512_16615_amd import inputs, llsa
 
-TOL = {"f32": dict(out=1e-4, lse=1e-4), "bf16": dict(out=2e-2, lse=1e-3)}
+BF16_ULP = 0.0          # no magnitude-scaled term: the plain bound holds on every shape tested (largest error seen 1.6e-2)
+TOL = {"f32": dict(out=1e-4, lse=1e-4, ulp=0.0), "bf16": dict(out=2e-2, lse=1e-3, ulp=BF16_ULP)}
+STATS: dict = {}        # output kind -> observed figures over every comparison of the session
 
 
 def make_inputs(cfg: dict, seed: int):
@@ -114,16 +117,50 @@ def check_indices(cfg, gpu, ref, b, h, x):
     return free_diff, excused
 
 
-def max_err(got: np.ndarray, ref: np.ndarray):
+def check_close(name, got, ref, tol, ulp=0.0):
+    """Asserts |got - ref| <= tol + ulp * |ref| element-wise; returns the plain max-abs error."""
     err = np.abs(got.astype(np.float64) - ref)
-    scaled = err / np.maximum(1.0, np.abs(ref))
-    return float(err.max()), float(scaled.max())
+    aref = np.abs(ref)
+    over = err - ulp * aref                      # what is left for the plain tolerance
+    kind = (name.split("(")[0].strip(), "ulp" if ulp > 0 else "plain", tol)
+    st = STATS.setdefault(kind, dict(max_abs_err=0.0, max_ref=0.0, max_err_minus_ulp_term=-1.0, elements=0,
+                                     above_plain_tol=0, worst=""))
+    e = float(err.max())
+    if e > st["max_abs_err"]:
+        st["max_abs_err"], st["worst"] = e, name
+    st["max_ref"] = max(st["max_ref"], float(aref.max()))
+    st["max_err_minus_ulp_term"] = max(st["max_err_minus_ulp_term"], float(over.max()))
+    st["elements"] += int(err.size)
+    st["above_plain_tol"] += int((err > tol).sum())
+    assert float(over.max()) <= tol, (f"{name}: max-abs err {e:.3e}, {int((over > tol).sum())} elements beyond "
+                                      f"{tol} + {ulp:.2e}*|ref| (max |ref| {float(aref.max()):.3e})")
+    return e
 
 
-def check_close(name, got, ref, tol):
-    err, scaled = max_err(got, ref)
-    assert scaled <= tol, f"{name}: max-abs err {err:.3e} (scaled {scaled:.3e}) > {tol}"
-    return err
+def dump_stats(path):
+    import json
+    rows = [dict(output=k[0], rule=k[1], tol=k[2], **v) for k, v in sorted(STATS.items())]
+    if rows:
+        with open(path, "w") as f:
+            json.dump(rows, f, indent=1)
+
+
+def oracle_backward_threads(Q, Kp, Vp, idx_cat, dO, g, Le, threads=16, reweight=1, scale=None):
+    """The oracle's backward of one head with the query rows split into `threads` ranges run on host threads
+    (the C call releases the interpreter lock): each range's fp64 share of dQ / dK / dV over the whole pyramid,
+    summed here, then the pooling adjoint.  Same arithmetic as orc.backward up to fp64 summation order."""
+    Kc, Vc = orc.cat_pyramid(Kp), orc.cat_pyramid(Vp)
+    cuts = [g.N * i // threads for i in range(threads + 1)]
+    ranges = [(a, b) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    tot = None
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for part in ex.map(lambda r: orc.attn_bwd(Q, Kc, Vc, idx_cat, dO, g, Le, reweight, scale, rows=r), ranges):
+            if tot is None:
+                tot = list(part)
+            else:
+                for t_, p_ in zip(tot, part):
+                    t_ += p_
+    return {"dQ": tot[0], "dK": orc.unpool(tot[1], g), "dV": orc.unpool(tot[2], g)}
 
 
 # ---- large shapes: the oracle checks sampled rows, properties cover every head ----
@@ -185,11 +222,11 @@ def sampled_parity(cfg, gpu, x, heads, n_row_chunks=6, chunk=32, full_backward_h
             o, lse = orc.attn_fwd(x["Q"][b, h], Kc, Vc, idx, g, Le, rows=(s0, s0 + chunk))
             dq, _, _ = orc.attn_bwd(x["Q"][b, h], Kc, Vc, idx, x["dO"][b, h], g, Le, rows=(s0, s0 + chunk))
             sl = slice(s0, s0 + chunk)
-            check_close(f"O{(b, h, s0)}", f32(gpu["O"][b, h, sl]), o[sl], tol["out"])
+            check_close(f"O{(b, h, s0)}", f32(gpu["O"][b, h, sl]), o[sl], tol["out"], tol["ulp"])
             check_close(f"LSE{(b, h, s0)}", f32(gpu["LSE"][b, h, sl]), lse[sl], tol["lse"])
-            check_close(f"dQ{(b, h, s0)}", f32(gpu["dQ"][b, h, sl]), dq[sl], tol["out"])
+            check_close(f"dQ{(b, h, s0)}", f32(gpu["dQ"][b, h, sl]), dq[sl], tol["out"], tol["ulp"])
         if full_backward_head == (b, h):
-            bw = orc.backward(x["Q"][b, h], Kp, Vp, idx, x["dO"][b, h], g, Le=Le)
+            bw = oracle_backward_threads(x["Q"][b, h], Kp, Vp, idx, x["dO"][b, h], g, Le)
             for name in ("dQ", "dK", "dV"):
-                err = check_close(f"{name}{(b, h)}", f32(gpu[name][b, h]), bw[name], tol["out"])
+                err = check_close(f"{name}{(b, h)}", f32(gpu[name][b, h]), bw[name], tol["out"], tol["ulp"])
                 print(f"{cfg['name']} full-head {name} max-abs err {err:.3e}")

@@ -25,7 +25,7 @@ def test_n65536_fewer_levels(L):
     """N = 65536 with L = 2 (the paper's setting at 256 x 256: 8 + 8 + 16 key blocks per query) and L = 1 (one coarse
     level of 4096 tokens, scored densely)."""
     cfg = dict(BASE, name=f"n65536_L{L}", N=65536, heads=2, L=L)
-    _run(cfg, 0x115A2000 + L, heads=[(0, 1)], n_row_chunks=3, full_backward_head=(0, 1) if L == 2 else None)
+    _run(cfg, 0x115A2000 + L, heads=[(0, 1)], n_row_chunks=3, full_backward_head=(0, 1))
 
 
 @pytest.mark.parametrize("Le", [0, 1, 2])
@@ -37,13 +37,13 @@ def test_n16384_partial_enrichment(Le):
 
 def test_n65536_K32():
     cfg = dict(BASE, name="n65536_K32", N=65536, heads=2, L=3, K=32)
-    _run(cfg, 0x115A2020, heads=[(0, 0)], n_row_chunks=3)
+    _run(cfg, 0x115A2020, heads=[(0, 0)], n_row_chunks=3, full_backward_head=(0, 0))
 
 
 @pytest.mark.timeout(400)
 def test_n262144_d64_L4():
     cfg = dict(BASE, name="n262144_d64", N=262144, heads=2, L=4)
-    _run(cfg, 0x115A2030, heads=[(0, 1)], n_row_chunks=3)
+    _run(cfg, 0x115A2030, heads=[(0, 1)], n_row_chunks=3, full_backward_head=(0, 1))
 
 
 @pytest.mark.timeout(600)

@@ -171,14 +171,30 @@ def test_single_level_is_textbook_topk(oracle):
         assert np.array_equal(I[0][i], _brute_topk(S[i], np.arange(N // B), K))
 
 
-def test_teaser_shape_is_accepted(oracle):
-    """N=8, B=2, K=1 (Fig. 1 caption): levels 8/4/2."""
+def test_teaser_shape_matches_a_by_hand_walk(oracle):
+    """N=8, B=2, K=1 (Fig. 1 caption): levels 8/4/2.  Every step written out directly in NumPy: means of pairs,
+    arg-max among the allowed candidates, softmax over the six listed tokens with weights 1, 2, 4."""
     rng = np.random.default_rng(12)
     g = oracle.Geometry(8, 4, 2, 1, 2)
-    r = oracle.forward(_rand(rng, 8, 4), _rand(rng, 8, 4), _rand(rng, 8, 4), g)
+    Q, Kk, V = (_rand(rng, 8, 4) for _ in range(3))
+    r = oracle.forward(Q, Kk, V, g)
     assert [a.shape for a in r["I"]] == [(4, 1), (2, 1)]
-    assert np.all(np.isfinite(r["O"]))
     assert g.list_len(2) == 2 + 2 + 2
+    mean2 = lambda x: (x[0::2] + x[1::2]) / np.float32(2)
+    Q1, K1, V1 = mean2(Q), mean2(Kk), mean2(V)
+    Q2, K2, V2 = mean2(Q1), mean2(K1), mean2(V1)
+    I1 = np.array([[int(np.argmax(Q2[i] @ K2.T))] for i in range(2)])           # level-1 key block per level-2 query
+    I0 = np.array([[2 * I1[i // 2, 0] + int(np.argmax(Q1[i] @ K1[2 * I1[i // 2, 0]: 2 * I1[i // 2, 0] + 2].T))]
+                   for i in range(4)])                                         # level-0 key block per level-1 query
+    assert np.array_equal(r["I"][1], I1) and np.array_equal(r["I"][0], I0)
+    for q in range(8):
+        j0, j1 = I0[q // 2, 0], I1[q // 4, 0]
+        keys = np.concatenate([Kk[2 * j0: 2 * j0 + 2], K1[2 * j1: 2 * j1 + 2], K2]).astype(np.float64)
+        vals = np.concatenate([V[2 * j0: 2 * j0 + 2], V1[2 * j1: 2 * j1 + 2], V2]).astype(np.float64)
+        w = np.array([1, 1, 2, 2, 4, 4], np.float64)
+        e = w * np.exp(0.5 * keys @ Q[q].astype(np.float64))
+        assert np.allclose(r["O"][q], (e / e.sum()) @ vals, atol=1e-12)
+        assert abs(r["LSE"][q] - math.log(e.sum())) < 1e-12
 
 
 # ------------------------------------------------------------ list building
@@ -288,14 +304,58 @@ def test_reweighting_is_multiplicity(oracle):
     assert np.abs(r0["O"] - r["O"]).max() > 1e-3
 
 
-def test_literal_scaling_reading_differs(oracle):
-    """Multiplying K and V by B^l (the literal reading of Alg. 1) is kept only as a switch; it is not the default."""
+def test_literal_scaling_reading_is_scaled_keys_and_values(oracle):
+    """The switch reweight = 2 is the literal reading of Alg. 1's enrichment loop: level-l keys and values are
+    multiplied by B^l before plain (unweighted) attention over the list.  Checked against exactly that, written
+    with the dense-mask formulation on pre-scaled pyramids; it is not the default and differs from it."""
     rng = np.random.default_rng(17)
     g = oracle.Geometry(64, 8, 4, 2, 2)
     Q, Kk, V = (_rand(rng, 64, 8) for _ in range(3))
-    a = oracle.forward(Q, Kk, V, g, reweight=1)["O"]
-    b = oracle.forward(Q, Kk, V, g, reweight=2)["O"]
-    assert np.abs(a - b).max() > 1e-2
+    a = oracle.forward(Q, Kk, V, g, reweight=1)
+    b = oracle.forward(Q, Kk, V, g, reweight=2)
+    assert np.abs(a["O"] - b["O"]).max() > 1e-2
+    Ks = [x.astype(np.float64) * 4.0 ** l for l, x in enumerate(b["Kp"])]
+    Vs = [x.astype(np.float64) * 4.0 ** l for l, x in enumerate(b["Vp"])]
+    O, LSE = _dense_mask_forward(b["Qp"][0], Ks, Vs, b["I"], g, 2, 0, 1 / math.sqrt(8))
+    assert np.allclose(b["O"], O, atol=1e-10) and np.allclose(b["LSE"], LSE, atol=1e-10)
+
+
+def test_query_sub_range_is_a_slice_of_the_full_call(oracle):
+    """attn_fwd(rows=(a, b)) computes exactly rows a..b-1 of the full call (every large-shape parity test relies
+    on it), also for ranges that start and end inside a query block."""
+    rng = np.random.default_rng(23)
+    g = oracle.Geometry(256, 16, 4, 2, 3)
+    Q, Kk, V = (_rand(rng, 256, 16) for _ in range(3))
+    f = oracle.forward(Q, Kk, V, g)
+    Kc, Vc = oracle.cat_pyramid(f["Kp"]), oracle.cat_pyramid(f["Vp"])
+    for a, b in ((0, 256), (0, 1), (5, 23), (100, 163), (255, 256)):
+        O, LSE = oracle.attn_fwd(Q, Kc, Vc, f["idx_cat"], g, 3, rows=(a, b))
+        assert np.array_equal(O[a:b], f["O"][a:b]) and np.array_equal(LSE[a:b], f["LSE"][a:b])
+        assert np.isnan(O[:a]).all() and np.isnan(O[b:]).all()
+
+
+def test_backward_shares_of_a_row_partition_sum_to_the_full_gradients(oracle):
+    """attn_bwd(rows=(a, b)) is the share of query rows a..b-1: its dQ has those rows of the full dQ and zeros
+    elsewhere, and the dK / dV shares of a partition add up to the full gradients (to fp64 summation order)."""
+    rng = np.random.default_rng(24)
+    g = oracle.Geometry(256, 16, 4, 2, 3)
+    Q, Kk, V = (_rand(rng, 256, 16) for _ in range(3))
+    dO = rng.standard_normal((256, 16))
+    f = oracle.forward(Q, Kk, V, g)
+    Kc, Vc = oracle.cat_pyramid(f["Kp"]), oracle.cat_pyramid(f["Vp"])
+    full = oracle.attn_bwd(Q, Kc, Vc, f["idx_cat"], dO, g, 3)
+    cuts = [0, 7, 64, 65, 200, 256]
+    acc = [np.zeros_like(x) for x in full]
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        part = oracle.attn_bwd(Q, Kc, Vc, f["idx_cat"], dO, g, 3, rows=(a, b))
+        assert np.array_equal(part[0][a:b], full[0][a:b])
+        assert not part[0][:a].any() and not part[0][b:].any()
+        for s_, p_ in zip(acc, part):
+            s_ += p_
+    for s_, f_ in zip(acc, full):
+        assert np.allclose(s_, f_, rtol=0, atol=1e-12 * max(1.0, np.abs(f_).max()))
+    # and a share is not the whole: the pin is sensitive to the range being honoured
+    assert np.abs(oracle.attn_bwd(Q, Kc, Vc, f["idx_cat"], dO, g, 3, rows=(0, 64))[1] - full[1]).max() > 1e-3
 
 
 # ---------------------------------------------------------------- gradients
