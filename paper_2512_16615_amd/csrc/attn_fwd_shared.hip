@@ -23,6 +23,8 @@ __device__ __forceinline__ u32x4 gload16(const char *base, unsigned off) {
     return *reinterpret_cast<gvec_ptr>(reinterpret_cast<const __attribute__((address_space(1))) char *>(
         reinterpret_cast<uintptr_t>(base)) + off);
 }
+constexpr float kLazy = 12.f;       // a query's softmax reference is raised only when a logit exceeds it by 2^kLazy
+
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
     union { u32x4 u; bf16x8 b; } c;
     c.u = v;
@@ -55,7 +57,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 
     bf16x8 qop[NB][KS];
     f32x4 acc[NB][NT];
-    float m[NB], lsum[NB];
+    float m[NB], mthr[NB], lsum[NB];                                  // reference, reference + kLazy, this lane's row-sum share
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
         const uint16_t *qrow = Q + (bh * N + (blk0 + NB * wave + b) * 16 + i16) * D + g * 8;
@@ -63,39 +65,33 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
         for (int s = 0; s < KS; ++s) qop[b][s] = ld_bf16x8(qrow + 32 * s);
 #pragma unroll
         for (int n = 0; n < NT; ++n) acc[b][n] = f32x4{0.f, 0.f, 0.f, 0.f};
-        m[b] = -INFINITY;
+        m[b] = mthr[b] = -INFINITY;
         lsum[b] = 0.f;
     }
 
-    // softmax update of query block b for one tile (s0 / s1: S^T of the two halves) and O^T += V^T P^T
-    // with the V tile at `vt` (row-major, STRIDE bytes per key row)
+    // softmax update of query block b for one tile (s0 / s1: raw S^T of the two halves) and O^T += V^T P^T
+    // with the V tile at `vt` (row-major, VS bytes per key row).  The running reference m[b] of a query is not its
+    // exact maximum: it is raised (and the accumulators rescaled) only when a logit exceeds it by more than kLazy
+    // (log2 units), so probabilities stay below 2^kLazy, which costs fp32 / bf16 no precision, and a tile's usual
+    // cost is a lane-local maximum and one compare.  Scale, level weight and reference are folded into the one
+    // multiply-add in front of the exponential.
     auto softmax_pv = [&](auto bsel, f32x4 s0, f32x4 s1, int c0, int c1, float b0, float b1, const char *vt, auto vstride) {
         constexpr int b = decltype(bsel)::value;
         constexpr int VS = decltype(vstride)::value;                  // bytes between the V tile's key rows
         f32x4 s[2] = {s0, s1};
-        const float b2[2] = {b0, b1};
-        const int c[2] = {c0, c1};
-        float mx = -INFINITY;
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                s[h][r] = fmaf(s[h][r], sc2, b2[h]);
-                mx = fmaxf(mx, s[h][r]);
-            }
-        if (c[0] < 16 || c[1] < 16) {                                 // ragged or absent block: mask, redo the max
-            mx = -INFINITY;
+        if (c0 < 16 || c1 < 16) {                                     // ragged or absent block: mask
+            const int c[2] = {c0, c1};
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
+                for (int r = 0; r < 4; ++r)
                     if (4 * g + r >= c[h]) s[h][r] = -INFINITY;
-                    mx = fmaxf(mx, s[h][r]);
-                }
         }
-        mx = rows_max(mx);
-        if (__builtin_amdgcn_ballot_w64(mx > m[b]) != 0) {            // some row's maximum rose: rescale
-            const float m_new = fmaxf(m[b], mx);
+        const float mx0 = fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3]));
+        const float mx1 = fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3]));
+        const float z = fmaxf(fmaf(mx0, sc2, b0), fmaf(mx1, sc2, b1));       // this lane's largest logit (log2 units)
+        if (__builtin_amdgcn_ballot_w64(z > mthr[b]) != 0) {          // some row outgrew its reference: rescale
+            const float m_new = fmaxf(m[b], rows_max(z));
             const float alpha = __builtin_amdgcn_exp2f(m[b] - m_new);
             lsum[b] *= alpha;
 #pragma unroll
@@ -103,12 +99,14 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[b][n][r] *= alpha;
             m[b] = m_new;
+            mthr[b] = m_new + kLazy;
         }
+        const float cb[2] = {b0 - m[b], b1 - m[b]};
 #pragma unroll
         for (int h = 0; h < 2; ++h)
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                s[h][r] = __builtin_amdgcn_exp2f(s[h][r] - m[b]);
+                s[h][r] = __builtin_amdgcn_exp2f(fmaf(s[h][r], sc2, cb[h]));
                 lsum[b] += s[h][r];
             }
         const bf16x8 pop = pack8(s[0], s[1]);
@@ -141,19 +139,37 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
     if (nbc > 0) {
         BlockTable ctab;                                              // lane j: coarse block 64 * chunk + j
         ctab.fill(t, bh, blk0, c_begin, 0, lane, D);
+        // Staging round r of this wave: 64 consecutive 16-byte chunks of the [K | V] tile, i.e. 64 / PARTS key rows of
+        // one half of K or of V, the same choice for the whole wave.
+        // (d = 64: one round, waves 0-3 stage K, waves 4-7 V; d = 128: round 0 stages K, round 1 V.)
         u32x4 sreg[RND];
+        int s_half[RND];
+        unsigned s_off[RND];
+#pragma unroll
+        for (int r = 0; r < RND; ++r) {
+            const int key0 = ((64 * wave + 512 * r) % (32 * PARTS)) / PARTS;   // the wave's first key row in round r
+            s_half[r] = key0 >> 4;
+            s_off[r] = (unsigned)((((key0 & 15) + lane / PARTS) * D + (lane % PARTS) * 8) * 2);
+        }
+        const bool v_wave = RND == 1 && wave >= 4;
+        uint64_t sptr = v_wave ? ctab.vptr : ctab.kptr;               // d = 64: the tensor this wave stages
         auto load_shared = [&](int u) {                               // coarse blocks 2u, 2u + 1 -> registers
-            if (u > 0 && ((2 * u) & 63) == 0) ctab.fill(t, bh, blk0, c_begin, (2 * u) >> 6, lane, D);
+            if (u > 0 && ((2 * u) & 63) == 0) {
+                ctab.fill(t, bh, blk0, c_begin, (2 * u) >> 6, lane, D);
+                sptr = v_wave ? ctab.vptr : ctab.kptr;
+            }
 #pragma unroll
             for (int r = 0; r < RND; ++r) {
-                const int cc = tid + 512 * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
-                const int key = c / PARTS, part = c % PARTS;
-                const int h = __builtin_amdgcn_readfirstlane(key >> 4);               // uniform within a wave
-                const int j = (2 * u + h < nbc) ? 2 * u + h : 2 * u;
-                const int cnt = (2 * u + h < nbc) ? ctab.count(j & 63) : 0;
-                const char *src = which ? ctab.V(j & 63) : ctab.K(j & 63);
-                const int row = min(key & 15, max(cnt, 1) - 1);
-                sreg[r] = gload16(src, (unsigned)((row * D + part * 8) * 2));
+                const bool have = 2 * u + s_half[r] < nbc;
+                const int j = (have ? 2 * u + s_half[r] : 2 * u) & 63;
+                const int cnt = have ? ctab.count(j) : 0;
+                const char *src = RND == 1 ? BlockTable::rl_ptr(sptr, j) : (r == 0 ? ctab.K(j) : ctab.V(j));
+                unsigned off = s_off[r];
+                if (cnt < 16) {                                       // ragged or absent block: re-read its last valid row
+                    const int row = min((int)(off / (D * 2)), max(cnt, 1) - 1);
+                    off = (unsigned)(row * D * 2) + off % (D * 2);
+                }
+                sreg[r] = gload16(src, off);
             }
         };
         auto store_shared = [&](int buf) {

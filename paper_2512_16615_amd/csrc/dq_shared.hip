@@ -111,19 +111,37 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
     if (nbc > 0) {
         BlockTable ctab;
         ctab.fill(t, bh, blk0, c_begin, 0, lane, D);
+        // Staging round r of this wave: 64 consecutive 16-byte chunks of the [K | V] tile, i.e. 64 / PARTS key rows of
+        // one half of K or of V, the same choice for the whole wave (d = 64: one round, waves 0-3 stage K, waves 4-7
+        // V; d = 128: round 0 stages K, round 1 V).
         u32x4 sreg[RND];
+        int s_half[RND];
+        unsigned s_off[RND];
+#pragma unroll
+        for (int r = 0; r < RND; ++r) {
+            const int key0 = ((64 * wave + 512 * r) % (32 * PARTS)) / PARTS;   // the wave's first key row in round r
+            s_half[r] = key0 >> 4;
+            s_off[r] = (unsigned)((((key0 & 15) + lane / PARTS) * D + (lane % PARTS) * 8) * 2);
+        }
+        const bool v_wave = RND == 1 && wave >= 4;
+        uint64_t sptr = v_wave ? ctab.vptr : ctab.kptr;               // d = 64: the tensor this wave stages
         auto load_shared = [&](int u) {
-            if (u > 0 && ((2 * u) & 63) == 0) ctab.fill(t, bh, blk0, c_begin, (2 * u) >> 6, lane, D);
+            if (u > 0 && ((2 * u) & 63) == 0) {
+                ctab.fill(t, bh, blk0, c_begin, (2 * u) >> 6, lane, D);
+                sptr = v_wave ? ctab.vptr : ctab.kptr;
+            }
 #pragma unroll
             for (int r = 0; r < RND; ++r) {
-                const int cc = tid + 512 * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
-                const int key = c / PARTS, part = c % PARTS;
-                const int h = __builtin_amdgcn_readfirstlane(key >> 4);
-                const int j = (2 * u + h < nbc) ? 2 * u + h : 2 * u;
-                const int cnt = (2 * u + h < nbc) ? ctab.count(j & 63) : 0;
-                const char *src = which ? ctab.V(j & 63) : ctab.K(j & 63);
-                const int row = min(key & 15, max(cnt, 1) - 1);
-                sreg[r] = gload16b(src, (unsigned)((row * D + part * 8) * 2));
+                const bool have = 2 * u + s_half[r] < nbc;
+                const int j = (have ? 2 * u + s_half[r] : 2 * u) & 63;
+                const int cnt = have ? ctab.count(j) : 0;
+                const char *src = RND == 1 ? BlockTable::rl_ptr(sptr, j) : (r == 0 ? ctab.K(j) : ctab.V(j));
+                unsigned off = s_off[r];
+                if (cnt < 16) {                                       // ragged or absent block: re-read its last valid row
+                    const int row = min((int)(off / (D * 2)), max(cnt, 1) - 1);
+                    off = (unsigned)(row * D * 2) + off % (D * 2);
+                }
+                sreg[r] = gload16b(src, off);
             }
         };
         auto store_shared = [&](int buf) {
