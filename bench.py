@@ -58,7 +58,7 @@ def cpu_baseline(cfg, x, threads):
     dt = time.perf_counter() - t0
     fwd, bwd = algorithmic_flops(cfg, g.list_len(g.L))
     flops = (fwd + bwd) * len(heads) / (cfg["batch"] * cfg["heads"])
-    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": len(heads), "kind": "oracle",
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": len(heads), "nproc": os.cpu_count(), "kind": "oracle",
             "sample": f"{len(heads)} of {cfg['batch'] * cfg['heads']} heads of the same workload, forward+backward, "
                       f"one head per thread, {dt:.1f} s"}
 
@@ -95,6 +95,20 @@ def device_inputs(cfg, seed, threads=16, keep_host=False):
             dev[n][b, h].copy_(torch.from_numpy(v))          # rounds to nearest even for bf16 I/O
     host = {n: dev[n].float().cpu().numpy() for n in dev} if keep_host else None
     return dev, host
+
+
+def step_events(fn, steps):
+    """K calls of fn, each bracketed by two HIP events on the current stream (which is the stream the library is
+    given): (median, min) milliseconds per call.  L2 / Infinity Cache are not flushed between the calls."""
+    import torch
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in ev)
+    return ms[len(ms) // 2], ms[0]
 
 
 def timed(fn, steps, warmup, graph):
@@ -179,7 +193,7 @@ def sweep_cases(which):
         out.append((group, dict(base, name=f"{group}_N{N}_L{L}_Le{L if Le is None else Le}_K{K}", N=N, L=L, K=K,
                                 heads=heads_for[N]), Le))
 
-    if which in ("n", "all"):
+    if which in ("n", "all", "mask"):
         for N in (4096, 16384, 65536, 262144, 1048576):
             add("n", N, deepest[N])
     if which in ("L", "all"):
@@ -224,14 +238,35 @@ def run_sweep(args):
                "kv_backward_ms": (st.get("dkv_coarse") or 0.0) + (st.get("dkv_fine") or 0.0) + (st.get("index_transpose") or 0.0),
                "stages_ms": st}
         row["kv_backward_mtokens_per_s"] = cfg["N"] * cfg["heads"] / row["kv_backward_ms"] / 1e3
+        # Sec. 5.4 / Fig. 4: key/value backward of level 0 alone, lists from Alg. 2 against lists from a dense
+        # T x T block mask (built and scanned inside the timed call); the mask must fit (here: up to 40 GB)
+        T = cfg["N"] // cfg["B"]
+        row["kv0_csc_ms"] = row["kv0_mask_ms"] = None
+        if group == "n" or args.sweep == "mask":
+            llsa_mod = case.llsa
+            a = (case.Q, case.K, case.V, case.dO, case.LSE, case.idx, case.ws)
+            dK0, dV0 = torch.empty_like(case.Q), torch.empty_like(case.Q)
+            case.step()                                        # D and the pooled levels in the workspace
+            row["kv0_csc_ms"] = timed(lambda: llsa_mod.kv_backward_level0(case.plan, False, *a, dK0=dK0, dV0=dV0), steps, 1, False)[0]
+            if cfg["heads"] * T * T <= 40e9:
+                mask = torch.empty(case.plan.batch * case.plan.heads * T * T + 256, dtype=torch.uint8, device="cuda")
+                row["kv0_mask_ms"] = timed(lambda: llsa_mod.kv_backward_level0(case.plan, True, *a, mask=mask, dK0=dK0, dV0=dV0),
+                                           steps, 1, False)[0]
+                del mask
+            for k in ("kv0_csc_ms", "kv0_mask_ms"):
+                if row[k]:
+                    row[k.replace("_ms", "_mtokens_per_s")] = cfg["N"] * cfg["heads"] / row[k] / 1e3
         rows.append(row)
         print(json.dumps(row), flush=True)
         del case
-    hdr = f"{'case':34s} {'M':>5s} {'fwd ms':>9s} {'f+b ms':>9s} {'fwd TF/s':>9s} {'f+b TF/s':>9s} {'f+b Mtok/s':>11s} {'KV-bwd Mtok/s':>14s}"
+    hdr = (f"{'case':34s} {'M':>5s} {'fwd ms':>9s} {'f+b ms':>9s} {'fwd TF/s':>9s} {'f+b TF/s':>9s} {'f+b Mtok/s':>11s} "
+           f"{'KV-bwd Mtok/s':>14s} {'kv0 csc ms':>11s} {'kv0 mask ms':>12s}")
     print(hdr, file=sys.stderr)
+    fmt = lambda v: f"{v:.3f}" if v else "-"
     for r in rows:
         print(f"{r['case']:34s} {r['gathered_tokens_per_query']:5d} {r['fwd_ms']:9.3f} {r['fwd_bwd_ms']:9.3f} {r['fwd_tflops']:9.1f} "
-              f"{r['fwd_bwd_tflops']:9.1f} {r['fwd_bwd_mtokens_per_s']:11.1f} {r['kv_backward_mtokens_per_s']:14.1f}", file=sys.stderr)
+              f"{r['fwd_bwd_tflops']:9.1f} {r['fwd_bwd_mtokens_per_s']:11.1f} {r['kv_backward_mtokens_per_s']:14.1f} "
+              f"{fmt(r['kv0_csc_ms']):>11s} {fmt(r['kv0_mask_ms']):>12s}", file=sys.stderr)
 
 
 def main():
@@ -255,7 +290,9 @@ def main():
                     help="keep the backward on the caller's stream (no fork onto the plan's auxiliary stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 512 MiB (to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--sweep", default=None, choices=["n", "L", "Le", "K", "B", "all"],
+    ap.add_argument("--pool-cache", action="store_true",
+                    help="only time the pooling stage warm (back to back) and with the caches flushed by a 1 GiB copy between calls")
+    ap.add_argument("--sweep", default=None, choices=["n", "L", "Le", "K", "B", "all", "mask"],
                     help="run the shape sweep instead of the headline workload")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -300,6 +337,28 @@ def main():
         case.step()
     torch.cuda.synchronize()
     fwd_flops, bwd_flops = algorithmic_flops(cfg, case.M)
+    if args.pool_cache:
+        # pooling alone: back to back (its 400 MB of input were just read by the previous call: what stays in the
+        # 256 MB Infinity Cache is warm), and after a 1 GiB copy that evicts L2 and Infinity Cache
+        pool_bytes = 3.0 * cfg["batch"] * cfg["heads"] * cfg["N"] * cfg["d"] * (2 if bf16 else 4) * (1.0 + 1.0 / (cfg["B"] - 1))
+        junk_a = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda")
+        junk_b = torch.empty_like(junk_a)
+        res = {}
+        for mode in ("warm", "flushed"):
+            ev = []
+            for _ in range(args.steps):
+                if mode == "flushed":
+                    junk_b.copy_(junk_a)
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                llsa.pool(case.plan, case.Q, case.K, case.V, case.ws)
+                b.record()
+                ev.append((a, b))
+            torch.cuda.synchronize()
+            ms = sorted(a.elapsed_time(b) for a, b in ev)
+            res[mode] = {"median_ms": ms[len(ms) // 2], "min_ms": ms[0], "gbps_at_median": pool_bytes / ms[len(ms) // 2] / 1e6}
+        print(json.dumps({"pool_all_levels": res, "algorithmic_bytes": pool_bytes, "workload": cfg["name"]}))
+        return
     stage = args.stage
     if stage == "auto":      # the longest single kernel of the step, from one untimed pass that brackets every stage
         st = case.stages(2)
@@ -316,6 +375,7 @@ def main():
     st = llsa.stage_timing_end()
     kern_ms = st[stage][0] / max(st[stage][1], 1)
     ms_per_step, mode = eager_ms, "eager launches"
+    median_ms, min_ms = step_events(case.step, args.steps)     # per-step HIP-event brackets: spread of the same step
 
     # The library neither allocates nor synchronises, so a whole step can be replayed from a HIP graph, which
     # removes the host launch gaps between its ~25 kernels.  Same kernels, same buffers, K replays timed.
@@ -329,26 +389,45 @@ def main():
     bhNd = cfg["batch"] * cfg["heads"] * cfg["N"] * cfg["d"]
     elt = 2 if bf16 else 4
     per_level_pairs = 2.0 * cfg["d"] * cfg["N"] * cfg["batch"] * cfg["heads"] * (case.plan.levels[0].K_l * cfg["B"])
-    work = {  # stage -> (bound, algorithmic flops or bytes of one launch)
-        "attn_fwd": ("mfma", fwd_flops),
-        "dq": ("mfma", 1.5 * fwd_flops),                      # S, dP, dQ = dS K: three contractions over the list
-        "dkv_fine": ("mfma", 4.0 * per_level_pairs),          # S, dP, dV, dK over the level-0 pairs
-        "pool": ("hbm", 3.0 * bhNd * elt * (1.0 + 1.0 / (cfg["B"] - 1))),
+    n_pooled = sum(cfg["N"] // cfg["B"] ** l for l in range(1, cfg["L"] + 1))
+    sel_bytes = 0.0                                           # pooled Q, K read once, gathered candidate rows, indices written
+    for l in range(1, cfg["L"] + 1):
+        n_l = cfg["N"] // cfg["B"] ** l
+        cand = n_l if l == cfg["L"] else case.plan.levels[l].K_l * cfg["B"]
+        k_out = case.plan.levels[l - 1].K_l
+        sel_bytes += cfg["batch"] * cfg["heads"] * (2.0 * n_l * cfg["d"] * elt + (n_l / cfg["B"]) * cand * cfg["d"] * elt
+                                                    + n_l * k_out * 4.0)
+    # stage -> (bound, ALGORITHMIC flops or bytes of one launch, contractions the kernels execute / the method defines)
+    work = {
+        "attn_fwd": ("mfma", fwd_flops, "2 / 2"),
+        "dq": ("mfma", 1.5 * fwd_flops, "3 / 3"),             # S, dP, dQ = dS K
+        "dkv_fine": ("mfma", 2.0 * per_level_pairs, "4 / 2"), # dV, dK (S and dP are recomputed: executed, not counted)
+        "dkv_coarse": ("mfma", fwd_flops - 2.0 * per_level_pairs if case.Le >= 1 else 0.0, "4 / 2"),
+        "pool": ("hbm", 3.0 * bhNd * elt * (1.0 + 1.0 / (cfg["B"] - 1)), None),
+        "select": ("hbm", sel_bytes, None),
     }
-    bound, amount = work.get(stage, ("mfma", 0.0))
+    bound, amount, _ = work.get(stage, ("mfma", 0.0, None))
     if args.force_generic or not bf16:
         roof_bound, peak, unit = ("alu", PEAK_F32_TFLOPS, "TFLOP/s") if bound == "mfma" else ("hbm", PEAK_HBM_GBPS, "GB/s")
     else:
         roof_bound, peak, unit = ("mfma", PEAK_BF16_TFLOPS, "TFLOP/s") if bound == "mfma" else ("hbm", PEAK_HBM_GBPS, "GB/s")
     achieved = amount / (kern_ms * 1e-3) / (1e12 if unit == "TFLOP/s" else 1e9) if kern_ms > 0 else 0.0
     roofline = {"kernel": stage, "bound": roof_bound, "achieved": achieved, "peak": peak, "unit": unit,
-                "frac": achieved / peak, "traffic": measured_traffic(stage, cfg["name"], cfg["kind"]), "kernel_ms": kern_ms}
+                "frac": achieved / peak, "traffic": measured_traffic(stage, cfg["name"], cfg["kind"]), "kernel_ms": kern_ms,
+                "traffic_source": "profiles/hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, "
+                                  "recorded beforehand (counters cannot be read inside the run)"}
+    # what this GPU delivers on nothing but MFMAs / on a plain copy, and the fraction against that as well
+    peaks = llsa.measured_peaks()
+    measured_peak = peaks["mfma_bf16_tflops"] if unit == "TFLOP/s" else peaks["copy_gbps"]
+    roofline["measured_peak"] = measured_peak
+    roofline["frac_of_measured_peak"] = achieved / measured_peak if measured_peak > 0 else None
 
     out = {
         "metric": "llsa_fwd_bwd_effective_tflops_n65536_h16_d64_bf16" if args.config == 3 else
                   f"llsa_fwd_bwd_effective_tflops_{cfg['name']}",
         "value": (fwd_flops + bwd_flops) / (ms_per_step * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median": median_ms, "ms_per_step_min": min_ms, "caches": "warm (no flush between steps)",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32", "data": "synthetic",
         "config": {"workload": f"BASELINE configs[{args.config}] {cfg['name']}: batch {cfg['batch']}, heads {cfg['heads']}, "
@@ -358,10 +437,27 @@ def main():
                    "launch": mode, "eager_ms_per_step": eager_ms, "graph_ms_per_step": graph_ms,
                    "streams": "caller's stream only" if args.single_stream else "caller's stream + one auxiliary stream inside llsa_backward"},
         "roofline": roofline,
+        "measured_peaks": peaks,
     }
 
+    # every stage of the step against its own roofline (one more pass outside the timed region; bracketing every
+    # stage keeps the backward on one stream, so index_transpose is not hidden here as it is in the timed step)
+    st_all = case.stages(min(args.steps, 10))
+    kernels = {}
+    for name, (b, amt, contr) in work.items():
+        ms = st_all.get(name)
+        if not ms or amt <= 0:
+            continue
+        mf = b == "mfma" and bf16 and not args.force_generic
+        pk, un = (PEAK_BF16_TFLOPS, "TFLOP/s") if mf else (PEAK_F32_TFLOPS, "TFLOP/s") if b == "mfma" else (PEAK_HBM_GBPS, "GB/s")
+        ach = amt / (ms * 1e-3) / (1e12 if un == "TFLOP/s" else 1e9)
+        kernels[name] = {"ms": ms, "bound": "mfma" if mf else "alu" if b == "mfma" else "hbm", "achieved": ach, "unit": un,
+                         "frac": ach / pk}
+        if contr:
+            kernels[name]["contractions_executed_over_algorithmic"] = contr
+    out["kernels"] = kernels
     if args.all_stages:
-        out["stages_ms"] = case.stages(args.steps)
+        out["stages_ms"] = st_all
 
     if args.dense_compare:
         import torch.nn.functional as F

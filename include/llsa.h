@@ -36,7 +36,8 @@ extern "C" {
 typedef enum {
     LLSA_OK = 0,
     LLSA_ERR_NULL = 1,        /* a required pointer is NULL                              */
-    LLSA_ERR_BAD_SHAPE = 2,   /* N not divisible by B^L, L < 1, Le outside 0..L, K < 1...*/
+    LLSA_ERR_BAD_SHAPE = 2,   /* N not divisible by B^L, L < 1, Le outside 0..L, K < 1...; a tensor, LSE or
+                                 indices pointer not 16-byte aligned, a workspace not 256-byte aligned */
     LLSA_ERR_UNSUPPORTED = 3, /* a (d, B, K, dtype, size) combination no kernel handles  */
     LLSA_ERR_WORKSPACE = 4,   /* llsa_forward_static: the plan needs more than the static workspace */
     LLSA_ERR_RUNTIME = 5      /* a HIP launch failed                                     */
@@ -147,6 +148,32 @@ size_t llsa_static_workspace_bytes(void);
 llsa_status llsa_forward_static(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O,
                                 float *LSE, int32_t *indices, void *hip_stream);
 
+/*
+ * Layer glue fused with the first compression step (Sec. 5.2, "Training Settings": RoPE and QK-Norm sit in front
+ * of the attention layer; Alg. 1, compression loop).  One pass over the pre-norm Q and K writes the level-0
+ * tensors the layer consumes and their level-1 means, so they are not read back for pooling; V is pooled as usual;
+ * then every remaining pooled level is filled, exactly as llsa_pool would on (Qout, Kout, V).
+ *   per token t (position within its head) and tensor X in {Q, K}:
+ *     y[c]        = Xpre[c] / sqrt(mean_c(Xpre[c]^2) + eps) * gamma_X[c]              (QK-Norm: RMS norm over d)
+ *     Xout[2i]    = y[2i] * cos[t][i] - y[2i+1] * sin[t][i]
+ *     Xout[2i+1]  = y[2i] * sin[t][i] + y[2i+1] * cos[t][i]                           (RoPE on adjacent channel pairs)
+ *   Qpre, Kpre, V  in : [batch, heads, N, d] of desc.dtype
+ *   gamma_q, gamma_k in : [d] fp32;   cos_table, sin_table in : [N, d / 2] fp32, shared by all heads (the caller
+ *                    fills them for its token order: 1-D positions, or the two axes of a pixel grid)
+ *   Qout, Kout    out : [batch, heads, N, d] of desc.dtype (fp32 arithmetic, one rounding); may not alias the inputs
+ *   workspace         : >= llsa_plan_workspace_bytes(plan, 0); holds the pooled levels of (Qout, Kout, V) afterwards
+ * Follow it with llsa_forward_pooled.  Errors: LLSA_ERR_NULL; LLSA_ERR_BAD_SHAPE for eps < 0 or misaligned pointers.
+ */
+llsa_status llsa_qknorm_rope_pool(const llsa_plan_t *plan, const void *Qpre, const void *Kpre, const void *V,
+                                  const float *gamma_q, const float *gamma_k, const float *cos_table,
+                                  const float *sin_table, float eps, void *Qout, void *Kout, void *workspace,
+                                  void *hip_stream);
+
+/* llsa_forward without its compression loop (Alg. 1, selection and enrichment loops only): `workspace` already
+   holds the pooled levels of Q, K, V, from llsa_qknorm_rope_pool or llsa_pool.  Same outputs as llsa_forward. */
+llsa_status llsa_forward_pooled(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O,
+                                float *LSE, int32_t *indices, void *workspace, void *hip_stream);
+
 /* ---- the steps of the path one by one (same kernels; used for step-wise parity checks) ---- */
 
 /* Hierarchical compression (Alg. 1, first loop): fills the pooled levels 1..L of Q, K, V in `workspace`. */
@@ -180,6 +207,24 @@ llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices
 llsa_status llsa_reorder(int64_t batch_heads, int64_t N, int32_t d, int32_t dtype, int32_t inverse, const void *in,
                          void *out, void *hip_stream);
 
+/* ---- key/value backward of level 0 alone, with its key-major lists built two ways (benchmark comparator) ----
+ * Sec. 5.4, "Efficient Backward Implementation" (Fig. 4) compares the key/value backward on the lists of Alg. 2 with
+ * the mask-based baseline of earlier Top-K methods: the indices are turned into a dense binary T x T block mask
+ * (T = N / B) and the backward scans it to skip the unmarked blocks.  Both are here, in front of the same dK / dV
+ * kernel:  via_mask = 0: Alg. 2 (count, scan, fill; O(T K));  via_mask = 1: zero the mask, mark the listed
+ * (key block, query block) pairs, scan every key block's T bytes and append the marked query blocks (O(T^2)).
+ *   Q, K, V, dO, LSE, indices in : as for llsa_backward (bf16 plans that run the MFMA kernels only)
+ *   workspace                    : a backward workspace on which llsa_backward has run for these tensors (the call
+ *                                  reads D = rowsum(dO * O) from it and overwrites level 0's lists)
+ *   mask                         : device, llsa_kv_backward_mask_bytes(plan) bytes (via_mask = 1; else may be NULL)
+ *   dK0, dV0                 out : [batch, heads, N, d]: the gradient reaching K and V through level 0 alone
+ *                                  (without the share of the pooled levels)
+ * Errors: LLSA_ERR_NULL, LLSA_ERR_BAD_SHAPE (alignment), LLSA_ERR_UNSUPPORTED (a plan on the portable kernels). */
+size_t llsa_kv_backward_mask_bytes(const llsa_plan_t *plan);
+llsa_status llsa_kv_backward_level0(const llsa_plan_t *plan, int32_t via_mask, const void *Q, const void *K, const void *V,
+                                    const void *dO, const float *LSE, const int32_t *indices, void *mask,
+                                    void *workspace, void *dK0, void *dV0, void *hip_stream);
+
 /* ---- per-stage timing for benchmarks (Sec. 5.4 reports kernel-level speed; this is how it is read here) ----
  * Stages: 0 pool, 1 select, 2 attention forward, 3 D = rowsum(dO*O), 4 index transpose, 5 dQ,
  * 6 dK/dV of the coarse levels, 7 un-pooling, 8 dK/dV of level 0.
@@ -193,6 +238,14 @@ int32_t llsa_stage_count(void);
 const char *llsa_stage_name(int32_t stage);
 llsa_status llsa_stage_timing_begin(int32_t stage, int32_t max_calls);
 llsa_status llsa_stage_timing_end(double *ms_sum, int32_t *brackets);
+
+/* ---- measured peaks of this GPU, for roofline fractions against what the chip delivers and not only the data sheet ----
+ * llsa_calibrate_mfma: `workgroups` workgroups of 4 waves, each wave 8 * iters bf16 MFMAs of 16 x 16 x 32 (16384 FLOP
+ * each) on registers only; the caller times the launch: FLOP = workgroups * 4 * 8 * iters * 16384.  `out`: device,
+ * at least 4 bytes, never written.  llsa_calibrate_copy: a plain copy of `bytes` (a multiple of 16) device bytes,
+ * 16 per thread; traffic = 2 * bytes. */
+llsa_status llsa_calibrate_mfma(float *out, int32_t iters, int32_t workgroups, void *hip_stream);
+llsa_status llsa_calibrate_copy(const void *src, void *dst, int64_t bytes, void *hip_stream);
 
 const char *llsa_status_string(llsa_status s);
 

@@ -257,6 +257,25 @@ def reorder(x: np.ndarray, inverse: bool = False) -> np.ndarray:
     return out
 
 
+# ------------------------------------------------------------------ layer glue (Sec. 5.2, "Training Settings")
+
+def qknorm_rope(x: np.ndarray, gamma: np.ndarray, cos: np.ndarray, sin: np.ndarray, eps: float = 1e-6) -> np.ndarray:
+    """QK-Norm followed by RoPE on one head ``x [N, d]``, fp64.  The paper names the two operators and cites them
+    without giving their form; the forms taken here are the ones of the cited works: the norm divides every token by
+    the root mean square of its d channels (plus ``eps`` under the root) and multiplies by a learned gain ``gamma
+    [d]``; the rotary embedding turns every adjacent channel pair ``(2i, 2i+1)`` of token t by the angle whose
+    cosine and sine are ``cos[t, i]``, ``sin[t, i]``."""
+    x = np.asarray(x, dtype=np.float64)
+    rms = np.sqrt((x * x).mean(axis=1, keepdims=True) + eps)
+    y = x / rms * np.asarray(gamma, dtype=np.float64)[None, :]
+    a, b = y[:, 0::2], y[:, 1::2]
+    c, s_ = np.asarray(cos, dtype=np.float64), np.asarray(sin, dtype=np.float64)
+    out = np.empty_like(y)
+    out[:, 0::2] = a * c - b * s_
+    out[:, 1::2] = a * s_ + b * c
+    return out
+
+
 # ------------------------------------------------------------------ whole layer
 
 def forward(Q, K, V, g: Geometry, Le: int | None = None, bf16: bool = False, reweight: int = 1,

@@ -377,8 +377,9 @@ int dkv_splits(const Plan &p, int l) {
     return (int)s;
 }
 
+// level0_alone: level 0's own gradient only, without the share of its parent tokens (the pooled levels' gradients)
 hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO, const float *LSE,
-                           const float *D, void *ws, void *dK, void *dV, hipStream_t s) {
+                           const float *D, void *ws, void *dK, void *dV, hipStream_t s, bool level0_alone) {
     char *w = static_cast<char *>(ws);
     DkvArgs a;
     const int64_t key_blocks = (int64_t)p.bh * ((p.n[l] + 15) / 16);
@@ -392,7 +393,7 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
     a.slab = key_blocks * 16 * p.d;
     a.partK = (float *)(w + p.part_off);
     a.partV = a.partK + (size_t)a.splits * a.slab;
-    const bool has_parent = (l == 0 && p.Le >= 1);
+    const bool has_parent = (l == 0 && p.Le >= 1 && !level0_alone);
     a.parK = has_parent ? (const float *)(w + p.dKacc_off[1]) : nullptr;
     a.parV = has_parent ? (const float *)(w + p.dVacc_off[1]) : nullptr;
     a.dK = (uint16_t *)dK; a.dV = (uint16_t *)dV;

@@ -153,6 +153,115 @@ hipError_t launch_pool(const Plan &p, const void *Q, const void *K, const void *
     return hipSuccess;
 }
 
+// ----------------------------------------------------------------------- layer glue fused with pooling
+// QK-Norm and RoPE in front of the layer (Sec. 5.2, "Training Settings") fused with the first step of the
+// compression loop of Alg. 1: one pass over the pre-norm tensor writes the level-0 tensor the layer consumes
+// and its level-1 mean, so the level-0 tensor is never read back for pooling.
+//   y[c]      = x[c] / sqrt(mean_c(x^2) + eps) * gamma[c]                      (per token, over the head dimension)
+//   out[2i]   = y[2i] cos[t][i] - y[2i+1] sin[t][i]
+//   out[2i+1] = y[2i] sin[t][i] + y[2i+1] cos[t][i]                             (t: token index within the head)
+// out is rounded to the I/O type; the level-1 token is pooled from those rounded values exactly as pool_kernel
+// does it (ascending fp32 sum, one division, one rounding), so it equals pool_kernel's result on `out` bit for bit.
+// One thread per (level-1 token, 16-byte channel vector); the d / VN threads of a token are neighbouring lanes and
+// reduce the sum of squares of a row with xor shuffles.  grid.y: 0 = Q, 1 = K.
+struct GlueArgs { const void *in[2]; void *out[2]; void *lvl1[2]; const float *gamma[2]; };
+
+template <class T>
+__global__ void __launch_bounds__(256) qknorm_rope_pool_kernel(GlueArgs a, const float *__restrict__ cos_t,
+                                                               const float *__restrict__ sin_t, float eps,
+                                                               int64_t n1_total, int64_t N, int d, int B) {
+    constexpr int VN = Vec<T>::n, ROWS = 4;                // rows of one token group in flight at a time
+    const int vpr = d / VN;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t t1 = idx / vpr;                          // level-1 token, flat over (batch, head)
+    const int cv = (int)(idx % vpr);
+    if (t1 >= n1_total) return;                            // whole token groups leave together (vpr divides 64)
+    const int y = blockIdx.y;
+    const T *in = static_cast<const T *>(a.in[y]) + (t1 * B) * (int64_t)d + cv * VN;
+    T *out = static_cast<T *>(a.out[y]) + (t1 * B) * (int64_t)d + cv * VN;
+    const int64_t tok0 = (t1 * B) % N;                     // position of the group's first token inside its head
+    float gam[VN];
+#pragma unroll
+    for (int e = 0; e < VN; ++e) gam[e] = a.gamma[y][cv * VN + e];
+    const float inv_d = 1.f / (float)d;
+    float s[VN];
+#pragma unroll
+    for (int e = 0; e < VN; ++e) s[e] = 0.f;
+    for (int r0 = 0; r0 < B; r0 += ROWS) {
+        float x[ROWS][VN], cs[ROWS][VN / 2], sn[ROWS][VN / 2];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            const int rr = min(r0 + r, B - 1);             // B need not be a multiple of ROWS: the tail re-reads
+            load_vec<T>(in + (int64_t)rr * d, x[r]);
+            const int64_t tab = (tok0 + rr) * (d / 2) + cv * (VN / 2);
+#pragma unroll
+            for (int e = 0; e < VN / 2; ++e) { cs[r][e] = cos_t[tab + e]; sn[r][e] = sin_t[tab + e]; }
+        }
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            float ss = 0.f;
+#pragma unroll
+            for (int e = 0; e < VN; ++e) ss = fmaf(x[r][e], x[r][e], ss);
+            for (int o = 1; o < vpr; o <<= 1) ss += __shfl_xor(ss, o, 64);
+            const float rinv = 1.f / sqrtf(fmaf(ss, inv_d, eps));
+            float o8[VN];
+#pragma unroll
+            for (int e = 0; e < VN / 2; ++e) {
+                const float y0 = x[r][2 * e] * rinv * gam[2 * e], y1 = x[r][2 * e + 1] * rinv * gam[2 * e + 1];
+                o8[2 * e] = to_f(from_f<T>(y0 * cs[r][e] - y1 * sn[r][e]));
+                o8[2 * e + 1] = to_f(from_f<T>(y0 * sn[r][e] + y1 * cs[r][e]));
+            }
+            if (r0 + r < B) {
+                store_vec<T>(out + (int64_t)(r0 + r) * d, o8);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) s[e] = s[e] + o8[e];
+            }
+        }
+    }
+    const float Bf = (float)B;
+#pragma unroll
+    for (int e = 0; e < VN; ++e) s[e] = __fdiv_rn(s[e], Bf);
+    store_vec<T>(static_cast<T *>(a.lvl1[y]) + t1 * (int64_t)d + cv * VN, s);
+}
+
+// Q and K through the fused kernel, V's level 1 and every level above through pool_kernel.
+hipError_t launch_qknorm_rope_pool(const Plan &p, const void *Qpre, const void *Kpre, const void *V,
+                                   const float *gamma_q, const float *gamma_k, const float *cos_t, const float *sin_t,
+                                   float eps, void *Qout, void *Kout, void *ws, hipStream_t s) {
+    char *w = static_cast<char *>(ws);
+    GlueArgs g;
+    g.in[0] = Qpre; g.in[1] = Kpre;
+    g.out[0] = Qout; g.out[1] = Kout;
+    g.lvl1[0] = w + p.pyr_off[0][1]; g.lvl1[1] = w + p.pyr_off[1][1];
+    g.gamma[0] = gamma_q; g.gamma[1] = gamma_k;
+    const int vn = 16 / p.elt;
+    const int64_t n1_total = (int64_t)p.bh * p.n[1];
+    const int64_t threads = n1_total * (p.d / vn);
+    dim3 grid((unsigned)((threads + 255) / 256), 2);
+    if (p.elt == 4) qknorm_rope_pool_kernel<float><<<grid, 256, 0, s>>>(g, cos_t, sin_t, eps, n1_total, p.N, p.d, p.B);
+    else qknorm_rope_pool_kernel<bf16_t><<<grid, 256, 0, s>>>(g, cos_t, sin_t, eps, n1_total, p.N, p.d, p.B);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const void *src[3] = {Qout, Kout, V};
+    for (int l = 1; l <= p.L; ++l) {
+        PoolArgs a;
+        int cnt = 0;
+        for (int x = (l == 1) ? 2 : 0; x < 3; ++x, ++cnt) {    // level 1 of Q and K is already there
+            a.in[cnt] = (l == 1) ? src[x] : (const void *)(w + p.pyr_off[x][l - 1]);
+            a.out[cnt] = w + p.pyr_off[x][l];
+        }
+        const int64_t n_out_total = (int64_t)p.bh * p.n[l];
+        const int64_t th = n_out_total * (p.d / vn);
+        dim3 pg((unsigned)((th + 255) / 256), cnt);
+        if (p.elt == 4) pool_kernel<float, 0><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else if (p.B == 16) pool_kernel<bf16_t, 16><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else                pool_kernel<bf16_t, 0><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 // ---------------------------------------------------------------------------------------------- selection
 // Alg. 1, selection loop, one level: every wave scores one level-l query token against its candidates
 // (all n_L tokens at the coarsest level, the K_l*B children of the parent's picks below it) and keeps the
@@ -609,6 +718,82 @@ hipError_t launch_dkv_generic(const Plan &p, const LevelTable &t, int l, const v
     else
         dkv_generic<bf16_t><<<grid, 256, 0, s>>>(t, l, (const bf16_t *)Q, (const bf16_t *)dO, LSE, D, C, Iq, ka, va, pk,
                                                  pv, (bf16_t *)dK, (bf16_t *)dV, p.N, total);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------- key-major lists through a dense block mask (comparator)
+// The mask-based baseline of Sec. 5.4 ("Efficient Backward Implementation", Fig. 4): the row-major lists I^(0) are
+// turned into a dense binary T x T block mask and the key/value backward scans it, skipping the unmarked blocks.
+// Here the mask is kept key-major (mask[key block][query block], one byte each: the layout that makes the scan a
+// contiguous read, the baseline's best case), and the scan of a key block's row writes the marked query blocks, in
+// ascending order, as that key's list -- the same (C, Iq) pair Alg. 2 produces in O(T K) -- so that the very same
+// dK / dV kernel runs behind both.  Work and memory of this path are O(T^2) per head.
+__global__ void __launch_bounds__(256) mask_zero_kernel(uint4 *mask16, int64_t n16) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n16) mask16[i] = make_uint4(0u, 0u, 0u, 0u);
+}
+// one thread per entry of I^(0): marks (key, query block) and counts the key's listers
+__global__ void __launch_bounds__(256) mask_mark_kernel(const int32_t *I, uint8_t *mask, int32_t *cnt, int64_t T, int Kl,
+                                                        int64_t total) {
+    const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (e >= total) return;
+    const int64_t eph = T * Kl, bh = e / eph, row = (e % eph) / Kl;
+    const int32_t key = I[e];
+    mask[(bh * T + key) * T + row] = 1;
+    atomicAdd(&cnt[bh * T + key], 1);
+}
+// one wave per key block: scans its T mask bytes, 1024 at a time, and appends the marked query blocks to its list
+__global__ void __launch_bounds__(256) mask_scan_kernel(const uint8_t *mask, const int32_t *C, int32_t *Iq, int64_t T,
+                                                        int64_t eph, int64_t nk) {
+    const int lane = threadIdx.x & 63;
+    const int64_t kb = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);           // flat key block over (batch, head)
+    if (kb >= nk) return;
+    const int64_t bh = kb / T, key = kb % T;
+    const uint8_t *row = mask + kb * T;
+    int32_t *dst = Iq + bh * eph + C[bh * (T + 1) + key];
+    int written = 0;
+    for (int64_t base = 0; base < T; base += 1024) {
+        const int64_t i0 = base + 16 * lane;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (i0 + 16 <= T) v = *reinterpret_cast<const uint4 *>(row + i0);
+        else for (int k = 0; k < 16 && i0 + k < T; ++k) reinterpret_cast<uint8_t *>(&v)[k] = row[i0 + k];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        int mine = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) mine += __popc(w[k] & 0x01010101u);
+        int incl = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int y = __shfl_up(incl, o, 64);
+            if (lane >= o) incl += y;
+        }
+        int pos = written + incl - mine;
+#pragma unroll
+        for (int k = 0; k < 16; ++k)
+            if ((w[k >> 2] >> (8 * (k & 3))) & 1u) dst[pos++] = (int32_t)(i0 + k);
+        written += __shfl(incl, 63, 64);
+    }
+}
+
+// Level 0's key-major lists through the dense mask: C and Iq of level 0 in the backward workspace, as launch_csc.
+hipError_t launch_mask_lists(const Plan &p, const int32_t *indices, void *ws, void *mask, hipStream_t s) {
+    char *w = static_cast<char *>(ws);
+    const int64_t T = p.n[1], nk = T * p.bh, eph = T * p.Kl[0], total = eph * p.bh;
+    CscLevels a;
+    CscLevel &L = a.lv[0];
+    L.T = T; L.Kl = p.Kl[0]; L.eph = eph; L.total = total; L.nk = nk;
+    L.I = reinterpret_cast<const int32_t *>(reinterpret_cast<const char *>(indices) + p.idx_off[0]);
+    L.cnt = (int32_t *)(w + p.cnt_off[0]);
+    L.C = (int32_t *)(w + p.C_off[0]);
+    L.Iq = (int32_t *)(w + p.Iq_off[0]);
+    L.Iq_tmp = (int32_t *)(w + p.Iqtmp_off[0]);
+    const int64_t n16 = (nk * T + 15) / 16;
+    if (n16 / 256 >= ((int64_t)1 << 31)) return hipErrorInvalidValue;
+    mask_zero_kernel<<<dim3((unsigned)((n16 + 255) / 256)), 256, 0, s>>>(static_cast<uint4 *>(mask), n16);
+    csc_zero_kernel<<<dim3((unsigned)((nk + 255) / 256), 1), 256, 0, s>>>(a);
+    mask_mark_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, s>>>(L.I, static_cast<uint8_t *>(mask), L.cnt, T, L.Kl, total);
+    csc_scan_kernel<<<dim3(p.bh, 1), kScanThreads, 0, s>>>(a);
+    mask_scan_kernel<<<dim3((unsigned)((nk + 3) / 4)), 256, 0, s>>>(static_cast<const uint8_t *>(mask), L.C, L.Iq, T, eph, nk);
     return hipGetLastError();
 }
 

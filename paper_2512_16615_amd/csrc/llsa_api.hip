@@ -60,6 +60,9 @@ static llsa_status build_plan(const llsa_desc &d, Plan &p) {
     if (d.d != 16 && d.d != 32 && d.d != 64 && d.d != 128) return LLSA_ERR_UNSUPPORTED;
     if (d.B > 64 || d.K > 64 || d.L > kMaxL) return LLSA_ERR_UNSUPPORTED;
     if (d.N > ((int64_t)1 << 30) || (int64_t)d.batch * d.heads > (1 << 20)) return LLSA_ERR_UNSUPPORTED;
+    // launch grids are 32-bit counts of workgroups (at least 16 tokens each) and the key-major lists use 32-bit offsets
+    if ((int64_t)d.batch * d.heads * ((d.N + 15) / 16) >= ((int64_t)1 << 31)) return LLSA_ERR_UNSUPPORTED;
+    if ((d.N / d.B) * (int64_t)(d.K < d.N / d.B ? d.K : d.N / d.B) >= ((int64_t)1 << 31)) return LLSA_ERR_UNSUPPORTED;
     int64_t bl = 1;
     for (int l = 0; l < d.L; ++l) {
         bl *= d.B;
@@ -232,6 +235,10 @@ static llsa_status static_workspace(void **out) {
     return LLSA_OK;
 }
 
+// Every kernel moves 16-byte vectors and the workspace layout assumes a 256-byte aligned base.
+static bool misaligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+template <class... P> static bool any_misaligned16(P... ptrs) { return (misaligned(ptrs, 16) || ...); }
+
 extern "C" {
 
 llsa_status llsa_plan(const llsa_desc *desc, llsa_plan_t **out) {
@@ -289,10 +296,17 @@ int32_t llsa_plan_csc_info(const llsa_plan_t *plan, int32_t l, size_t *C_byte_of
     do {                                                 \
         if ((expr) != hipSuccess) return LLSA_ERR_RUNTIME; \
     } while (0)
+#define LLSA_TRY_ST(expr)                                \
+    do {                                                 \
+        const llsa_status st_ = (expr);                  \
+        if (st_ != LLSA_OK) return st_;                  \
+    } while (0)
+
 
 llsa_status llsa_pool(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *workspace,
                       void *hip_stream) {
     if (!plan || !Q || !K || !V || !workspace) return LLSA_ERR_NULL;
+    if (any_misaligned16(Q, K, V) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
     LLSA_TRY(launch_pool(plan->p, Q, K, V, workspace, true, (hipStream_t)hip_stream));
     return LLSA_OK;
 }
@@ -302,6 +316,7 @@ llsa_status llsa_select_level(const llsa_plan_t *plan, int32_t l, const void *wo
     if (!plan || !workspace || !out) return LLSA_ERR_NULL;
     if (l < 1 || l > plan->p.L) return LLSA_ERR_BAD_SHAPE;
     if (l < plan->p.L && !parent) return LLSA_ERR_NULL;
+    if (any_misaligned16(parent, out) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
     LLSA_TRY(launch_select(plan->p, l, workspace, parent, out, (hipStream_t)hip_stream));
     return LLSA_OK;
 }
@@ -309,6 +324,7 @@ llsa_status llsa_select_level(const llsa_plan_t *plan, int32_t l, const void *wo
 llsa_status llsa_attention(const llsa_plan_t *plan, const void *Q, const void *K, const void *V,
                            const int32_t *indices, const void *workspace, void *O, float *LSE, void *hip_stream) {
     if (!plan || !Q || !K || !V || !indices || !workspace || !O || !LSE) return LLSA_ERR_NULL;
+    if (any_misaligned16(Q, K, V, O, LSE, indices) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
     const Plan &p = plan->p;
     LevelTable t = make_level_table(p, K, V, indices, workspace);
     if (p.fast) LLSA_TRY(launch_attn_fwd_mfma(p, t, Q, O, LSE, (hipStream_t)hip_stream));
@@ -316,13 +332,43 @@ llsa_status llsa_attention(const llsa_plan_t *plan, const void *Q, const void *K
     return LLSA_OK;
 }
 
+static llsa_status forward_impl(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O, float *LSE,
+                                int32_t *indices, void *workspace, void *hip_stream, bool pool);
+
 llsa_status llsa_forward(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O, float *LSE,
                          int32_t *indices, void *workspace, void *hip_stream) {
     if (!plan || !Q || !K || !V || !O || !LSE || !indices || !workspace) return LLSA_ERR_NULL;
+    if (any_misaligned16(Q, K, V, O, LSE, indices) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
+    return forward_impl(plan, Q, K, V, O, LSE, indices, workspace, hip_stream, true);
+}
+
+llsa_status llsa_forward_pooled(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O, float *LSE,
+                                int32_t *indices, void *workspace, void *hip_stream) {
+    if (!plan || !Q || !K || !V || !O || !LSE || !indices || !workspace) return LLSA_ERR_NULL;
+    if (any_misaligned16(Q, K, V, O, LSE, indices) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
+    return forward_impl(plan, Q, K, V, O, LSE, indices, workspace, hip_stream, false);
+}
+
+llsa_status llsa_qknorm_rope_pool(const llsa_plan_t *plan, const void *Qpre, const void *Kpre, const void *V,
+                                  const float *gamma_q, const float *gamma_k, const float *cos_table,
+                                  const float *sin_table, float eps, void *Qout, void *Kout, void *workspace,
+                                  void *hip_stream) {
+    if (!plan || !Qpre || !Kpre || !V || !gamma_q || !gamma_k || !cos_table || !sin_table || !Qout || !Kout || !workspace)
+        return LLSA_ERR_NULL;
+    if (any_misaligned16(Qpre, Kpre, V, Qout, Kout, cos_table, sin_table) || misaligned(workspace, 256))
+        return LLSA_ERR_BAD_SHAPE;
+    if (!(eps >= 0.f)) return LLSA_ERR_BAD_SHAPE;
+    LLSA_TRY(launch_qknorm_rope_pool(plan->p, Qpre, Kpre, V, gamma_q, gamma_k, cos_table, sin_table, eps, Qout, Kout,
+                                     workspace, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
+static llsa_status forward_impl(const llsa_plan_t *plan, const void *Q, const void *K, const void *V, void *O, float *LSE,
+                                int32_t *indices, void *workspace, void *hip_stream, bool pool) {
     const Plan &p = plan->p;
     hipStream_t s = (hipStream_t)hip_stream;
     const int call = g_timer.on ? g_timer.fwd_calls++ : 0;
-    {
+    if (pool) {
         StageScope sc(kPool, call, s);
         LLSA_TRY(launch_pool(p, Q, K, V, workspace, true, s));
     }
@@ -353,6 +399,7 @@ llsa_status llsa_forward_static(const llsa_plan_t *plan, const void *Q, const vo
 
 llsa_status llsa_index_transpose(const llsa_plan_t *plan, const int32_t *indices, void *workspace, void *hip_stream) {
     if (!plan || !indices || !workspace) return LLSA_ERR_NULL;
+    if (any_misaligned16(indices) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
     const Plan &p = plan->p;
     LLSA_TRY(launch_csc(p, p.L - 1, indices, workspace, (hipStream_t)hip_stream));
     return LLSA_OK;
@@ -363,6 +410,7 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
                           void *workspace, void *hip_stream) {
     if (!plan || !Q || !K || !V || !O || !LSE || !indices || !dO || !dQ || !dK || !dV || !workspace)
         return LLSA_ERR_NULL;
+    if (any_misaligned16(Q, K, V, O, LSE, indices, dO, dQ, dK, dV) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
     const Plan &p = plan->p;
     hipStream_t s = (hipStream_t)hip_stream;
     char *w = static_cast<char *>(workspace);
@@ -385,47 +433,89 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     // and a level above their range is dense and has none), that is behind dQ, in the shadow of those kernels:
     // they are bound by LDS and leave wave slots and registers free, which dQ does not.  Otherwise it is beside dQ.
     const bool shadow = aux && p.group;
+    bool forked = false, lists_recorded = false, joined = false;
     auto transpose = [&]() -> llsa_status {
         const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
         if (aux) {
             LLSA_TRY(hipEventRecord(aux->ev[0], s));
             LLSA_TRY(hipStreamWaitEvent(side, aux->ev[0], 0));
+            forked = true;
         }
         StageScope sc(kTranspose, call, side);              // bracketed on the stream it runs on
         LLSA_TRY(launch_csc(p, top_listed, indices, workspace, side));
-        if (aux) LLSA_TRY(hipEventRecord(aux->ev[1], side));
+        if (aux) {
+            LLSA_TRY(hipEventRecord(aux->ev[1], side));
+            lists_recorded = true;
+        }
         return LLSA_OK;
     };
-    if (!shadow) LLSA_TRY(transpose());
-    LevelTable t = make_level_table(p, K, V, indices, workspace);
-    {
-        StageScope sc(kDq, call, s);
-        if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, O, dO, LSE, D, dQ, s));
-        else LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
-    }
-    if (shadow) LLSA_TRY(transpose());
-    // the caller's stream waits for the key-major lists where it first reads them (which also joins the streams)
-    hipEvent_t lists = aux ? aux->ev[1] : nullptr;
-    if (lists && !shadow) LLSA_TRY(hipStreamWaitEvent(s, lists, 0));
-    // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
-    {
-        StageScope sc(kDkvCoarse, call, s);
-        if (p.group) {                                      // levels above the grouped kernel's range first
-            for (int l = p.Le; l > dkv_group_top(p); --l) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
-            LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, shadow ? lists : nullptr));
-        } else for (int l = p.Le; l >= 1; --l) {
-            if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
-            else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+    auto enqueue = [&]() -> llsa_status {
+        if (!shadow) LLSA_TRY_ST(transpose());
+        LevelTable t = make_level_table(p, K, V, indices, workspace);
+        {
+            StageScope sc(kDq, call, s);
+            if (p.fast) LLSA_TRY(launch_dq_mfma(p, t, Q, O, dO, LSE, D, dQ, s));
+            else LLSA_TRY(launch_dq_generic(p, t, Q, dO, LSE, D, dQ, s));
         }
+        if (shadow) LLSA_TRY_ST(transpose());
+        // the caller's stream waits for the key-major lists where it first reads them (which also joins the streams)
+        hipEvent_t lists = aux ? aux->ev[1] : nullptr;
+        if (lists && !shadow) {
+            LLSA_TRY(hipStreamWaitEvent(s, lists, 0));
+            joined = true;
+        }
+        // coarse levels first (fp32), fold them down level by level, then level 0 adds its parent's share
+        {
+            StageScope sc(kDkvCoarse, call, s);
+            if (p.group) {                                  // levels above the grouped kernel's range first
+                for (int l = p.Le; l > dkv_group_top(p); --l) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+                LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, shadow ? lists : nullptr));
+                if (shadow) joined = true;                  // the grouped launcher waits for the lists before its gathers
+            } else for (int l = p.Le; l >= 1; --l) {
+                if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+                else LLSA_TRY(launch_dkv_generic(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
+            }
+        }
+        {
+            StageScope sc(kUnpool, call, s);
+            if (!p.fast)                                    // the MFMA path folds this into its slab reduction
+                for (int l = p.Le; l >= 2; --l) LLSA_TRY(launch_unpool(p, l, workspace, s));
+        }
+        StageScope sc(kDkvFine, call, s);
+        if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
+        else LLSA_TRY(launch_dkv_generic(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
+        return LLSA_OK;
+    };
+    const llsa_status st = enqueue();
+    if (forked && !joined) {
+        // A launch failed after the fork: still lead the auxiliary stream back into the caller's, so that a stream
+        // capture in progress is not left with an unjoined branch.  Errors here cannot make the outcome worse.
+        if (!lists_recorded) (void)hipEventRecord(aux->ev[1], side);
+        (void)hipStreamWaitEvent(s, aux->ev[1], 0);
     }
-    {
-        StageScope sc(kUnpool, call, s);
-        if (!p.fast)                                        // the MFMA path folds this into its slab reduction
-            for (int l = p.Le; l >= 2; --l) LLSA_TRY(launch_unpool(p, l, workspace, s));
-    }
-    StageScope sc(kDkvFine, call, s);
-    if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
-    else LLSA_TRY(launch_dkv_generic(p, t, 0, Q, dO, LSE, D, workspace, dK, dV, s));
+    return st;
+}
+
+size_t llsa_kv_backward_mask_bytes(const llsa_plan_t *plan) {
+    if (!plan) return 0;
+    const size_t T = (size_t)plan->p.n[1];
+    return ((size_t)plan->p.bh * T * T + 255) & ~(size_t)255;
+}
+
+llsa_status llsa_kv_backward_level0(const llsa_plan_t *plan, int32_t via_mask, const void *Q, const void *K, const void *V,
+                                    const void *dO, const float *LSE, const int32_t *indices, void *mask,
+                                    void *workspace, void *dK0, void *dV0, void *hip_stream) {
+    if (!plan || !Q || !K || !V || !dO || !LSE || !indices || !workspace || !dK0 || !dV0 || (via_mask && !mask))
+        return LLSA_ERR_NULL;
+    if (any_misaligned16(Q, K, V, dO, LSE, indices, dK0, dV0, mask) || misaligned(workspace, 256)) return LLSA_ERR_BAD_SHAPE;
+    const Plan &p = plan->p;
+    if (!p.fast) return LLSA_ERR_UNSUPPORTED;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *w = static_cast<char *>(workspace);
+    if (via_mask) LLSA_TRY(launch_mask_lists(p, indices, workspace, mask, s));
+    else LLSA_TRY(launch_csc(p, 0, indices, workspace, s));
+    LevelTable t = make_level_table(p, K, V, indices, workspace);
+    LLSA_TRY(launch_dkv_mfma(p, t, 0, Q, dO, LSE, reinterpret_cast<const float *>(w + p.D_off), workspace, dK0, dV0, s, true));
     return LLSA_OK;
 }
 
@@ -442,6 +532,20 @@ llsa_status llsa_reorder(int64_t batch_heads, int64_t N, int32_t d, int32_t dtyp
     const int64_t bytes = batch_heads * N * row_bytes;
     if (a < b + bytes && b < a + bytes) return LLSA_ERR_BAD_SHAPE;      // the copy is not in place
     LLSA_TRY(launch_reorder(batch_heads, N, (int)row_bytes, bits, inverse ? 1 : 0, in, out, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
+llsa_status llsa_calibrate_mfma(float *out, int32_t iters, int32_t workgroups, void *hip_stream) {
+    if (!out) return LLSA_ERR_NULL;
+    if (iters < 1 || workgroups < 1 || workgroups > (1 << 20)) return LLSA_ERR_BAD_SHAPE;
+    LLSA_TRY(launch_peak_mfma(out, iters, workgroups, (hipStream_t)hip_stream));
+    return LLSA_OK;
+}
+
+llsa_status llsa_calibrate_copy(const void *src, void *dst, int64_t bytes, void *hip_stream) {
+    if (!src || !dst) return LLSA_ERR_NULL;
+    if (bytes < 16 || bytes % 16 != 0 || any_misaligned16(src, dst)) return LLSA_ERR_BAD_SHAPE;
+    LLSA_TRY(launch_peak_copy(src, dst, bytes, (hipStream_t)hip_stream));
     return LLSA_OK;
 }
 

@@ -58,11 +58,17 @@ LevelTable make_level_table(const Plan &p, const void *K0, const void *V0, const
 // ---- portable scalar kernels (any supported shape) ----
 hipError_t launch_pool(const Plan &p, const void *Q, const void *K, const void *V, void *ws, bool q_too,
                        hipStream_t s);
+// QK-Norm + RoPE of Q and K fused with level-1 pooling, then the remaining pooled levels (fills Qout, Kout and ws)
+hipError_t launch_qknorm_rope_pool(const Plan &p, const void *Qpre, const void *Kpre, const void *V,
+                                   const float *gamma_q, const float *gamma_k, const float *cos_t, const float *sin_t,
+                                   float eps, void *Qout, void *Kout, void *ws, hipStream_t s);
 hipError_t launch_select(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s);
 hipError_t launch_attn_fwd_generic(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                    hipStream_t s);
 hipError_t launch_bwd_pre(const Plan &p, const void *O, const void *dO, float *D, hipStream_t s);
 hipError_t launch_csc(const Plan &p, int top_level, const int32_t *I, void *ws, hipStream_t s);  // levels 0..top_level
+// level 0's key-major lists through a dense T x T block mask (`mask`: bh * T * T bytes, rounded up to 16) instead of Alg. 2
+hipError_t launch_mask_lists(const Plan &p, const int32_t *indices, void *ws, void *mask, hipStream_t s);
 hipError_t launch_dq_generic(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
                              const float *D, void *dQ, hipStream_t s);
 hipError_t launch_dkv_generic(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO,
@@ -72,11 +78,11 @@ hipError_t launch_unpool(const Plan &p, int l, void *ws, hipStream_t s);
 hipError_t launch_reorder(int64_t bh, int64_t N, int row_bytes, int bits, int inverse, const void *in, void *out,
                           hipStream_t s);
 
-// ---- fast selection (bf16, B = 16, <= 128 candidates, K <= 16) ----
+// ---- fast selection (bf16, B = 16 / 32 / 64, K <= 64; any number of candidates, 256 at a time) ----
 bool select_fast_ok(const Plan &p, int l);
 hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s);
 
-// ---- bf16 MFMA kernels (B = 16, d = 64 or 128) ----
+// ---- bf16 MFMA kernels (B = 16 / 32 / 64, d = 64 or 128, N % 64 == 0) ----
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);
 // variant that shares the coarse levels among the 16 sibling query blocks of a workgroup (d = 64, N % 256 == 0)
 hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
@@ -89,7 +95,7 @@ hipError_t launch_dq_shared(const Plan &p, const LevelTable &t, const void *Q, c
 // key-major dK/dV of level l; levels >= 1 also fold their split slabs and the level above into the
 // level's fp32 gradient buffer, so they must be launched from the coarsest level down
 hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void *Q, const void *dO, const float *LSE,
-                           const float *D, void *ws, void *dK, void *dV, hipStream_t s);
+                           const float *D, void *ws, void *dK, void *dV, hipStream_t s, bool level0_alone = false);
 int dkv_splits(const Plan &p, int l);    // workgroups sharing one key block's query list at level l
 // all coarse levels (dkv_group_top .. 1) at once, grouped by level-1 query block; fills the levels' fp32
 // gradients.  `lists` (or null): event after which the key-major lists are complete, recorded on another stream;
@@ -98,5 +104,9 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
                             const float *D, void *ws, hipStream_t s, hipEvent_t lists);
 void dkv_group_sizes(const Plan &p, size_t *slab_bytes, size_t *red_bytes);
 int dkv_group_top(const Plan &p);         // highest level the grouped kernel takes (the rest: split kernel)
+
+// ---- measured peaks for the benchmark (calibrate.hip) ----
+hipError_t launch_peak_mfma(float *out, int iters, int workgroups, hipStream_t s);
+hipError_t launch_peak_copy(const void *src, void *dst, int64_t bytes, hipStream_t s);
 
 }  // namespace llsa

@@ -111,6 +111,30 @@ def make_tensor(kind: str, seed: int, tensor: str, batch: int, heads: int, N: in
     return out
 
 
+def rope_tables(N: int, d: int, base: float = 10000.0) -> tuple[np.ndarray, np.ndarray]:
+    """Rotary-position tables ``(cos, sin)``, each ``[N, d // 2]`` fp32, for tokens in raster order: an input of the
+    layer glue, built by whoever owns the token order.  If N is a square W x W pixel grid the two axes share the
+    channel pairs (pairs ``0 .. d/4 - 1`` turn with the row y, pairs ``d/4 .. d/2 - 1`` with the column x, the usual
+    axial form for images), otherwise all pairs turn with the 1-D position; pair i of an axis with P pairs has the
+    frequency ``base ** (-i / P)``.  Angles are formed in fp64 and the tables rounded once to fp32."""
+    half = d // 2
+    W = math.isqrt(N)
+    t = np.arange(N, dtype=np.float64)
+    if W * W == N and half % 2 == 0:
+        P = half // 2
+        freq = base ** (-np.arange(P, dtype=np.float64) / P)
+        ang = np.concatenate([(t // W)[:, None] * freq[None, :], (t % W)[:, None] * freq[None, :]], axis=1)
+    else:
+        freq = base ** (-np.arange(half, dtype=np.float64) / half)
+        ang = t[:, None] * freq[None, :]
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
+
+
+def norm_gain(seed: int, which: str, d: int) -> np.ndarray:
+    """``[d]`` fp32 gain of the QK-Norm of ``which`` ("Q" or "K"): 1 + 0.1 N(0, 1), as after some training."""
+    return (1.0 + 0.1 * normal(seed, (TENSOR_IDS[which], 0, 0, 7), d)).astype(np.float32)
+
+
 # BASELINE.json's five configurations (index = position in its "configs" list).
 CONFIGS = [
     dict(name="tiny_fp32", batch=1, heads=1, d=32, N=256, B=4, K=2, L=3, dtype="f32", kind="gaussian"),

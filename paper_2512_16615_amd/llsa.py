@@ -34,7 +34,8 @@ EXPORTS = ["llsa_plan", "llsa_plan_destroy", "llsa_plan_workspace_bytes", "llsa_
            "llsa_plan_level_info", "llsa_plan_pyramid_info", "llsa_plan_csc_info", "llsa_forward", "llsa_backward",
            "llsa_pool", "llsa_select_level", "llsa_attention", "llsa_index_transpose", "llsa_reorder", "llsa_status_string",
            "llsa_stage_count", "llsa_stage_name", "llsa_stage_timing_begin", "llsa_stage_timing_end",
-           "llsa_static_workspace_bytes", "llsa_forward_static"]
+           "llsa_static_workspace_bytes", "llsa_forward_static", "llsa_qknorm_rope_pool", "llsa_forward_pooled",
+           "llsa_kv_backward_mask_bytes", "llsa_kv_backward_level0", "llsa_calibrate_mfma", "llsa_calibrate_copy"]
 
 
 def load():
@@ -66,6 +67,18 @@ def load():
     lib.llsa_forward_static.restype = ctypes.c_int
     lib.llsa_static_workspace_bytes.argtypes = []
     lib.llsa_static_workspace_bytes.restype = sz
+    lib.llsa_forward_pooled.argtypes = [vp] * 9
+    lib.llsa_forward_pooled.restype = ctypes.c_int
+    lib.llsa_qknorm_rope_pool.argtypes = [vp] * 8 + [ctypes.c_float] + [vp] * 4
+    lib.llsa_qknorm_rope_pool.restype = ctypes.c_int
+    lib.llsa_kv_backward_mask_bytes.argtypes = [vp]
+    lib.llsa_kv_backward_mask_bytes.restype = sz
+    lib.llsa_kv_backward_level0.argtypes = [vp, i32] + [vp] * 11
+    lib.llsa_kv_backward_level0.restype = ctypes.c_int
+    lib.llsa_calibrate_mfma.argtypes = [vp, i32, i32, vp]
+    lib.llsa_calibrate_mfma.restype = ctypes.c_int
+    lib.llsa_calibrate_copy.argtypes = [vp, vp, i64, vp]
+    lib.llsa_calibrate_copy.restype = ctypes.c_int
     lib.llsa_backward.argtypes = [vp] * 13
     lib.llsa_backward.restype = ctypes.c_int
     lib.llsa_pool.argtypes = [vp] * 6
@@ -208,6 +221,38 @@ def forward(p: Plan, Q, K, V, O=None, LSE=None, indices=None, workspace=None):
     return O, LSE, indices, workspace
 
 
+def qknorm_rope_pool(p: Plan, Qpre, Kpre, V, gamma_q, gamma_k, cos_table, sin_table, eps=1e-6, workspace=None):
+    """``llsa_qknorm_rope_pool``: returns ``(Qout, Kout, workspace)`` (workspace holds every pooled level)."""
+    for t, n in ((Qpre, "Qpre"), (Kpre, "Kpre"), (V, "V")):
+        _chk_tensor(p, t, n)
+    for t, shape, n in ((gamma_q, (p.d,), "gamma_q"), (gamma_k, (p.d,), "gamma_k"),
+                        (cos_table, (p.N, p.d // 2), "cos_table"), (sin_table, (p.N, p.d // 2), "sin_table")):
+        if not t.is_cuda or not t.is_contiguous() or t.dtype != torch.float32 or tuple(t.shape) != shape:
+            raise LlsaError(f"{n}: expected a contiguous cuda float32 tensor of shape {shape}")
+    Qout, Kout = torch.empty_like(Qpre), torch.empty_like(Kpre)
+    workspace = p.alloc_workspace(False, Qpre.device) if workspace is None else workspace
+    if workspace.numel() < p.workspace_bytes(False):
+        raise LlsaError("workspace too small")
+    _check(load().llsa_qknorm_rope_pool(p._h, _ptr(Qpre), _ptr(Kpre), _ptr(V), _ptr(gamma_q), _ptr(gamma_k),
+                                        _ptr(cos_table), _ptr(sin_table), ctypes.c_float(eps), _ptr(Qout), _ptr(Kout),
+                                        _ptr(workspace), _stream()), "llsa_qknorm_rope_pool")
+    return Qout, Kout, workspace
+
+
+def forward_pooled(p: Plan, Q, K, V, workspace, O=None, LSE=None, indices=None):
+    """``llsa_forward_pooled``: forward pass on pooled levels already in ``workspace``."""
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V")):
+        _chk_tensor(p, t, n)
+    O = torch.empty_like(Q) if O is None else O
+    LSE = torch.empty(p.batch, p.heads, p.N, dtype=torch.float32, device=Q.device) if LSE is None else LSE
+    indices = p.alloc_indices(Q.device) if indices is None else indices
+    if workspace.numel() < p.workspace_bytes(False) or indices.numel() * 4 < p.indices_bytes():
+        raise LlsaError("workspace or indices buffer too small")
+    _check(load().llsa_forward_pooled(p._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(indices),
+                                      _ptr(workspace), _stream()), "llsa_forward_pooled")
+    return O, LSE, indices
+
+
 def forward_static(p: Plan, Q, K, V, O, LSE, indices):
     """``llsa_forward_static``: forward pass on the library's static workspace; the caller passes every
     output buffer, and neither the binding nor the library allocates."""
@@ -235,6 +280,21 @@ def backward(p: Plan, Q, K, V, O, LSE, indices, dO, workspace, dQ=None, dK=None,
     _check(load().llsa_backward(p._h, _ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(LSE), _ptr(indices), _ptr(dO),
                                 _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(workspace), _stream()), "llsa_backward")
     return dQ, dK, dV
+
+
+def kv_backward_level0(p: Plan, via_mask: bool, Q, K, V, dO, LSE, indices, workspace, mask=None, dK0=None, dV0=None):
+    """``llsa_kv_backward_level0``: level 0's dK, dV with the key-major lists from Alg. 2 or from a dense block mask.
+    ``workspace`` must be the one a preceding ``backward`` call used (it holds D).  Returns ``(dK0, dV0, mask)``."""
+    for t, n in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
+        _chk_tensor(p, t, n)
+    if via_mask and mask is None:
+        mask = torch.empty(load().llsa_kv_backward_mask_bytes(p._h), dtype=torch.uint8, device=Q.device)
+    dK0 = torch.empty_like(Q) if dK0 is None else dK0
+    dV0 = torch.empty_like(Q) if dV0 is None else dV0
+    _check(load().llsa_kv_backward_level0(p._h, int(via_mask), _ptr(Q), _ptr(K), _ptr(V), _ptr(dO), _ptr(LSE),
+                                          _ptr(indices), _ptr(mask), _ptr(workspace), _ptr(dK0), _ptr(dV0), _stream()),
+           "llsa_kv_backward_level0")
+    return dK0, dV0, mask
 
 
 def pool(p: Plan, Q, K, V, workspace):
@@ -275,6 +335,30 @@ def reorder(x: torch.Tensor, inverse: bool = False, out: torch.Tensor | None = N
     out = torch.empty_like(x) if out is None else out
     _check(load().llsa_reorder(x.numel() // (N * d), N, d, dtype, int(inverse), _ptr(x), _ptr(out), _stream()), "llsa_reorder")
     return out
+
+
+def measured_peaks(mfma_iters: int = 20000, copy_bytes: int = 1 << 30, reps: int = 5) -> dict:
+    """Times ``llsa_calibrate_mfma`` (2048 workgroups: 8 per CU) and ``llsa_calibrate_copy`` with HIP events: the
+    bf16 MFMA rate and the copy bandwidth this GPU delivers, best of ``reps``."""
+    lib = load()
+    out = torch.zeros(4, dtype=torch.float32, device="cuda")
+    src = torch.zeros(copy_bytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    wgs = 2048
+    best = {"mfma": float("inf"), "copy": float("inf")}
+    for rep in range(reps + 1):
+        for name, call in (("mfma", lambda: lib.llsa_calibrate_mfma(_ptr(out), mfma_iters, wgs, _stream())),
+                           ("copy", lambda: lib.llsa_calibrate_copy(_ptr(src), _ptr(dst), copy_bytes, _stream()))):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            _check(call(), f"llsa_calibrate_{name}")
+            e1.record()
+            e1.synchronize()
+            if rep > 0:                                      # the first round warms up
+                best[name] = min(best[name], e0.elapsed_time(e1))
+    flop = wgs * 4 * 8 * mfma_iters * 16384.0
+    return {"mfma_bf16_tflops": flop / (best["mfma"] * 1e-3) / 1e12, "copy_gbps": 2.0 * copy_bytes / (best["copy"] * 1e-3) / 1e9,
+            "mfma_ms": best["mfma"], "copy_ms": best["copy"]}
 
 
 def stage_names() -> list[str]:

@@ -21,7 +21,7 @@ def llsa():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "llsa.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(llsa_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(llsa_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol(llsa):
@@ -134,3 +134,28 @@ def test_forward_static_checks_the_size_on_the_host(llsa):
     assert lib.llsa_forward_static(big._h, a, a, None, a, a, a, None) == 1
     headline = llsa.Plan(1, 16, 65536, 64, 16, 8, 3)
     assert headline.workspace_bytes(False) <= lib.llsa_static_workspace_bytes()
+
+
+def test_glue_entry_points_and_alignment_are_checked_on_the_host(llsa):
+    """NULL, a negative eps and misaligned pointers are refused before any launch, by every compute entry point."""
+    lib = llsa.load()
+    plan = llsa.Plan(1, 3, 4096, 64, 16, 8, 2)
+    a, odd = ctypes.c_void_p(4096), ctypes.c_void_p(4100)
+    eps = ctypes.c_float(1e-6)
+    assert lib.llsa_qknorm_rope_pool(plan._h, None, a, a, a, a, a, a, eps, a, a, a, None) == 1
+    assert lib.llsa_qknorm_rope_pool(plan._h, a, a, a, a, a, a, a, ctypes.c_float(-1.0), a, a, a, None) == 2
+    assert lib.llsa_qknorm_rope_pool(plan._h, odd, a, a, a, a, a, a, eps, a, a, a, None) == 2
+    assert lib.llsa_forward_pooled(plan._h, a, a, a, a, a, a, None, None) == 1
+    assert lib.llsa_forward(plan._h, a, odd, a, a, a, a, a, None) == 2
+    assert lib.llsa_forward(plan._h, a, a, a, a, a, a, ctypes.c_void_p(4096 + 16), None) == 2     # workspace: 256 bytes
+    assert lib.llsa_backward(plan._h, a, a, a, a, a, a, a, a, a, odd, a, None) == 2
+    assert lib.llsa_attention(plan._h, a, a, a, a, a, odd, a, None) == 2
+    assert lib.llsa_pool(plan._h, a, a, odd, a, None) == 2
+
+
+def test_plan_refuses_sizes_beyond_32_bit_grids(llsa):
+    """Launch grids and the key-major list offsets are 32-bit: a plan that would overflow them is refused."""
+    with pytest.raises(llsa.LlsaError) as e:
+        llsa.Plan(1 << 10, 1 << 10, 1 << 20, 64, 16, 8, 4)          # 2^20 heads x 2^16 tiles
+    assert "status 3" in str(e.value)
+    llsa.Plan(1, 4, 1 << 20, 64, 16, 8, 4)                           # the largest tested shape is fine

@@ -503,3 +503,80 @@ def test_index_reordering_round_trip_and_pooling_meaning(oracle):
             want = img[4 * py:4 * py + 4, 4 * px:4 * px + 4].reshape(16, d).mean(axis=0)
             t = int(np.nonzero(oracle.nested_order(W) == (4 * py) * W + 4 * px)[0][0]) // 16
             assert np.allclose(pooled[t], want, rtol=0, atol=1e-6)
+
+
+# ------------------------------------------------------ layer glue: QK-Norm and RoPE (Sec. 5.2, "Training Settings")
+
+def test_qknorm_is_unit_rms_and_scale_invariant(oracle):
+    """With unit gain and zero angles every token comes out with root mean square 1 (eps aside), whatever its
+    input scale; the gain multiplies channel-wise."""
+    rng = np.random.default_rng(31)
+    N, d = 64, 32
+    x = rng.standard_normal((N, d)) * rng.uniform(0.1, 30.0, (N, 1))
+    one, c, s = np.ones(d), np.ones((N, d // 2)), np.zeros((N, d // 2))
+    y = oracle.qknorm_rope(x, one, c, s, eps=0.0)
+    assert np.allclose(np.sqrt((y * y).mean(1)), 1.0, atol=1e-12)
+    assert np.allclose(oracle.qknorm_rope(7.5 * x, one, c, s, eps=0.0), y, atol=1e-12)
+    g = rng.uniform(0.5, 2.0, d)
+    assert np.allclose(oracle.qknorm_rope(x, g, c, s, eps=0.0), y * g, atol=1e-12)
+    # eps sits under the root, added to the mean square: a zero token stays zero, a tiny one is damped
+    assert not oracle.qknorm_rope(np.zeros((N, d)), one, c, s, eps=1e-6).any()
+    tiny = np.full((1, d), 1e-3)
+    assert np.allclose(oracle.qknorm_rope(tiny, one, c[:1], s[:1], eps=1e-6), 1e-3 / math.sqrt(1e-6 + 1e-6), atol=1e-12)
+
+
+def test_rope_rotates_adjacent_pairs(oracle):
+    """Quarter turn: (a, b) -> (-b, a); the rotation keeps every pair's length; it acts on pairs (2i, 2i+1)."""
+    rng = np.random.default_rng(32)
+    N, d = 16, 8
+    x = rng.standard_normal((N, d))
+    x /= np.sqrt((x * x).mean(1, keepdims=True))            # already unit RMS: the norm leaves it alone
+    one = np.ones(d)
+    q = oracle.qknorm_rope(x, one, np.zeros((N, d // 2)), np.ones((N, d // 2)), eps=0.0)
+    assert np.allclose(q[:, 0::2], -x[:, 1::2], atol=1e-12) and np.allclose(q[:, 1::2], x[:, 0::2], atol=1e-12)
+    ang = rng.uniform(0, 2 * math.pi, (N, d // 2))
+    r = oracle.qknorm_rope(x, one, np.cos(ang), np.sin(ang), eps=0.0)
+    assert np.allclose(r[:, 0::2] ** 2 + r[:, 1::2] ** 2, x[:, 0::2] ** 2 + x[:, 1::2] ** 2, atol=1e-12)
+    z = x[:, 0::2] + 1j * x[:, 1::2]                         # the same rotation as a complex product
+    w = z * np.exp(1j * ang)
+    assert np.allclose(r[:, 0::2], w.real, atol=1e-12) and np.allclose(r[:, 1::2], w.imag, atol=1e-12)
+
+
+def test_rope_scores_depend_on_relative_position_only(oracle):
+    """The defining property of the rotary embedding: with 1-D position tables, the score of a query at position m
+    and a key at position n depends on m - n only (same vectors, shifted positions, same score)."""
+    from paper_2512_16615_amd import inputs
+    rng = np.random.default_rng(33)
+    d, N = 16, 24                                           # 24 is no square: the tables are 1-D
+    cos, sin = inputs.rope_tables(N, d)
+    qv, kv = rng.standard_normal(d), rng.standard_normal(d)
+    Q = np.tile(qv, (N, 1))
+    Kk = np.tile(kv, (N, 1))
+    one = np.ones(d)
+    S = oracle.qknorm_rope(Q, one, cos, sin, 0.0) @ oracle.qknorm_rope(Kk, one, cos, sin, 0.0).T
+    for off in (-5, 0, 3):
+        diag = np.diagonal(S, offset=off)
+        assert np.allclose(diag, diag[0], atol=1e-5)          # fp32 tables
+    assert abs(S[0, 5] - S[5, 0]) > 1e-3                     # and it does depend on the sign of the offset
+
+
+def test_rope_tables_are_axial_on_a_pixel_grid():
+    """On a W x W grid the first half of the pairs turns with the row, the second half with the column."""
+    from paper_2512_16615_amd import inputs
+    W, d = 8, 16
+    cos, sin = inputs.rope_tables(W * W, d)
+    ang = np.arctan2(sin.astype(np.float64), cos.astype(np.float64)).reshape(W, W, d // 2)
+    assert np.allclose(ang[:, 0, : d // 4], ang[:, 5, : d // 4], atol=1e-6)        # row pairs ignore the column
+    assert np.allclose(ang[0, :, d // 4:], ang[6, :, d // 4:], atol=1e-6)          # column pairs ignore the row
+    assert np.allclose(ang[1, 0, 0], 1.0, atol=1e-6) and np.allclose(ang[0, 1, d // 4], 1.0, atol=1e-6)
+
+
+def test_glue_then_pool_is_mean_of_the_glued_block(oracle):
+    """The fused step is the glue followed by the compression loop's first step: nothing else."""
+    from paper_2512_16615_amd import inputs
+    rng = np.random.default_rng(34)
+    N, d, B = 64, 16, 4
+    x = rng.standard_normal((N, d)).astype(np.float32)
+    cos, sin = inputs.rope_tables(N, d)
+    y = oracle.qknorm_rope(x, np.ones(d), cos, sin).astype(np.float32)
+    assert np.allclose(oracle.pool(y, B, False), y.reshape(N // B, B, d).mean(1), atol=1e-6)
