@@ -290,6 +290,8 @@ def main():
                     help="keep the backward on the caller's stream (no fork onto the plan's auxiliary stream)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a plain device copy of 512 MiB (to scale rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--glue", action="store_true",
+                    help="only time llsa_qknorm_rope_pool (QK-Norm + RoPE fused with pooling) against llsa_pool")
     ap.add_argument("--pool-cache", action="store_true",
                     help="only time the pooling stage warm (back to back) and with the caches flushed by a 1 GiB copy between calls")
     ap.add_argument("--sweep", default=None, choices=["n", "L", "Le", "K", "B", "all", "mask"],
@@ -337,6 +339,29 @@ def main():
         case.step()
     torch.cuda.synchronize()
     fwd_flops, bwd_flops = algorithmic_flops(cfg, case.M)
+    if args.glue:
+        # the fused glue + pooling pass against pooling alone (what a separate glue kernel would have to be added to)
+        elt = 2 if bf16 else 4
+        bhNd = cfg["batch"] * cfg["heads"] * cfg["N"] * cfg["d"]
+        cos, sin = (torch.from_numpy(a).cuda() for a in inputs.rope_tables(cfg["N"], cfg["d"]))
+        gq, gk = (torch.from_numpy(inputs.norm_gain(1, w, cfg["d"])).cuda() for w in ("Q", "K"))
+        ws2 = case.plan.alloc_workspace(False)
+        res = {}
+        for name, fn in (("qknorm_rope_pool", lambda: llsa.qknorm_rope_pool(case.plan, case.Q, case.K, case.V, gq, gk, cos, sin, 1e-6, ws2)),
+                         ("pool", lambda: llsa.pool(case.plan, case.Q, case.K, case.V, case.ws))):
+            for _ in range(3):
+                fn()
+            med, mn = step_events(fn, args.steps)
+            res[name] = {"median_ms": med, "min_ms": mn}
+        pool_bytes = 3.0 * bhNd * elt * (1.0 + 1.0 / (cfg["B"] - 1))
+        glue_bytes = pool_bytes + 2.0 * bhNd * elt            # plus Qout and Kout written
+        res["qknorm_rope_pool"]["algorithmic_bytes"] = glue_bytes
+        res["qknorm_rope_pool"]["gbps_at_median"] = glue_bytes / res["qknorm_rope_pool"]["median_ms"] / 1e6
+        res["pool"]["algorithmic_bytes"] = pool_bytes
+        res["pool"]["gbps_at_median"] = pool_bytes / res["pool"]["median_ms"] / 1e6
+        res["unfused_estimate_bytes"] = pool_bytes + 4.0 * bhNd * elt   # a separate glue kernel reads and writes Q and K
+        print(json.dumps({"glue": res, "workload": cfg["name"]}))
+        return
     if args.pool_cache:
         # pooling alone: back to back (its 400 MB of input were just read by the previous call: what stays in the
         # 256 MB Infinity Cache is warm), and after a 1 GiB copy that evicts L2 and Infinity Cache
