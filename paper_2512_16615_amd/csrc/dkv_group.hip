@@ -86,21 +86,6 @@ __device__ __forceinline__ void stage_store(const StageRegs<D, NTHR> &r, char *q
     for (int k = 0; k < 512 / NTHR; ++k) st[tid + NTHR * k] = r.s[k];
 }
 
-// per-lane LDS offsets inside a 16-row slice (the swizzle key of a row depends only on the lane)
-template <int D> struct TileOffsets { int row[D / 32], tr[D / 16]; };
-template <int D> __device__ __forceinline__ TileOffsets<D> tile_offsets(int lane) {
-    using S = GShape<D>;
-    const int i16 = lane & 15, g = lane >> 4;
-    const int key_row = swz_key<D>(i16), key_tr = swz_key<D>(4 * g + (i16 >> 2));   // rows of a slice: i16 resp. 4g + i16 / 4
-    TileOffsets<D> o;
-#pragma unroll
-    for (int ks = 0; ks < S::KS; ++ks) o.row[ks] = i16 * S::ROWB + (((g + 4 * ks) ^ key_row) << 4);
-#pragma unroll
-    for (int n = 0; n < S::NT; ++n)
-        o.tr[n] = (4 * g + (i16 >> 2)) * S::ROWB + (((2 * n + ((i16 >> 1) & 1)) ^ key_tr) << 4) + ((i16 & 1) << 3);
-    return o;
-}
-
 // One key block held by a wave: its K / V rows as B operands, the level's log2 weight, its gradient sums.
 template <int D> struct BlockAcc {
     bf16x8 kop[D / 32], vop[D / 32];

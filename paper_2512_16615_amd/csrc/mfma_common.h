@@ -89,6 +89,24 @@ template <int D> __device__ __forceinline__ int swz_key(int r) {
     return D == 64 ? ((r >> 1) & 7) : (((r & 7) << 1) | ((r >> 3) & 1));
 }
 
+// Per-lane byte offsets of the MFMA operand reads inside a 16-row slice of such unpadded, swizzled rows (2 D bytes
+// each): row[ks] = the 16-byte row-wise read of row lane % 16, contraction step ks (A or B operand with the rows as
+// the 16-wide dimension); tr[n] = the address a lane supplies to the transposing 64-bit read for the n-th group of 16
+// channels (rows 4 (lane / 16) + (lane % 16) / 4).  The swizzle key of a row depends on the lane only.
+template <int D> struct TileOffsets { int row[D / 32], tr[D / 16]; };
+template <int D> __device__ __forceinline__ TileOffsets<D> tile_offsets(int lane) {
+    constexpr int ROWB = 2 * D;
+    const int i16 = lane & 15, g = lane >> 4;
+    const int key_row = swz_key<D>(i16), key_tr = swz_key<D>(4 * g + (i16 >> 2));
+    TileOffsets<D> o;
+#pragma unroll
+    for (int ks = 0; ks < D / 32; ++ks) o.row[ks] = i16 * ROWB + (((g + 4 * ks) ^ key_row) << 4);
+#pragma unroll
+    for (int n = 0; n < D / 16; ++n)
+        o.tr[n] = (4 * g + (i16 >> 2)) * ROWB + (((2 * n + ((i16 >> 1) & 1)) ^ key_tr) << 4) + ((i16 & 1) << 3);
+    return o;
+}
+
 // Workgroup id -> work item so that the workgroups one XCD receives (ids congruent modulo 8) cover a
 // contiguous range of work items: neighbouring query blocks gather overlapping keys, which then stay in
 // that XCD's L2.
