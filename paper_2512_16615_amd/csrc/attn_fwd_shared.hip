@@ -138,7 +138,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
     const int nbc = t.bseg[t.nlev] - c_begin;                         // coarse blocks
     if (nbc > 0) {
         BlockTable ctab;                                              // lane j: coarse block 64 * chunk + j
-        ctab.fill(t, bh, blk0, c_begin, 0, lane, D);
+        ctab.fill_once(t, bh, blk0, c_begin, lane, wave, D, reinterpret_cast<uint32_t *>(lds + 4 * TILE));
         // Staging round r of this wave: 64 consecutive 16-byte chunks of the [K | V] tile, i.e. 64 / PARTS key rows of
         // one half of K or of V, the same choice for the whole wave.
         // (d = 64: one round, waves 0-3 stage K, waves 4-7 V; d = 128: round 0 stages K, round 1 V.)

@@ -155,6 +155,27 @@ struct BlockTable {
             }
         }
     }
+    // The same table for every wave of a workgroup (same head, same list rows): wave 0 builds it, the others copy it
+    // from `tab` (64 x 24 bytes of LDS nobody else uses meanwhile).  Every thread of the workgroup must call this.
+    __device__ __forceinline__ void fill_once(const LevelTable &t, int64_t bh, int64_t blk, int base, int lane, int wave,
+                                              int d, uint32_t *tab) {
+        if (wave == 0) {
+            fill(t, bh, blk, base, 0, lane, d);
+            tab[lane] = (uint32_t)kptr;
+            tab[64 + lane] = (uint32_t)(kptr >> 32);
+            tab[128 + lane] = (uint32_t)vptr;
+            tab[192 + lane] = (uint32_t)(vptr >> 32);
+            tab[256 + lane] = __float_as_uint(bias2);
+            tab[320 + lane] = (uint32_t)cnt;
+        }
+        __syncthreads();
+        if (wave != 0) {
+            kptr = ((uint64_t)tab[64 + lane] << 32) | tab[lane];
+            vptr = ((uint64_t)tab[192 + lane] << 32) | tab[128 + lane];
+            bias2 = __uint_as_float(tab[256 + lane]);
+            cnt = (int)tab[320 + lane];
+        }
+    }
     static __device__ __forceinline__ const char *rl_ptr(uint64_t v, int j) {
         const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)v, j);
         const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), j);
