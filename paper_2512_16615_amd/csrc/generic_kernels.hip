@@ -80,73 +80,105 @@ template <class T> __device__ __forceinline__ float dot_row(const T *row, const 
 // Alg. 1, compression loop: out[t] = (x[tB] + x[tB+1] + ... + x[tB+B-1]) / B, summed in that order in
 // fp32, one IEEE division, one rounding to the I/O type.  The order is part of the contract: the
 // selection below is decided on these values, so they must not depend on the launch shape.
-struct PoolArgs { const void *in[3]; void *out[3]; };
+struct PoolArgs { const void *in[3]; void *out[3]; void *out2[3]; };
 
 // BC: block size known at compile time (the row loop is unrolled, so all B loads of a thread are in flight at once),
 // or 0 to take it from the argument.  Same order of additions either way.
-template <class T, int BC>
+// TWO: the workgroup also pools its own output once more (out2 = the level above): its 256 / (d / VN) output tokens
+// are whole groups of B, their rounded values pass through LDS and are summed in the same ascending order, so out2
+// is bit for bit what a second launch on `out` would write, without that launch.
+template <class T, int BC, bool TWO>
 __global__ void __launch_bounds__(256) pool_kernel(PoolArgs a, int64_t n_out_total, int d, int B_arg) {
     constexpr int VN = Vec<T>::n;
+    __shared__ float lvl[TWO ? 256 * VN : 1];
     const int B = BC ? BC : B_arg;
     const int vpr = d / VN;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t t = idx / vpr;
     const int cv = (int)(idx % vpr);
-    if (t >= n_out_total) return;
-    const T *in = static_cast<const T *>(a.in[blockIdx.y]) + (t * B) * (int64_t)d + cv * VN;
+    const bool live = t < n_out_total;
+    if (!TWO && !live) return;
     float s[VN];
 #pragma unroll
     for (int e = 0; e < VN; ++e) s[e] = 0.f;
-    if constexpr (BC != 0) {
-        float x[BC][VN];
+    if (live) {
+        const T *in = static_cast<const T *>(a.in[blockIdx.y]) + (t * B) * (int64_t)d + cv * VN;
+        if constexpr (BC != 0) {
+            float x[BC][VN];
 #pragma unroll
-        for (int r = 0; r < BC; ++r) load_vec<T>(in + (int64_t)r * d, x[r]);
+            for (int r = 0; r < BC; ++r) load_vec<T>(in + (int64_t)r * d, x[r]);
 #pragma unroll
-        for (int r = 0; r < BC; ++r)
-#pragma unroll
-            for (int e = 0; e < VN; ++e) s[e] = s[e] + x[r][e];
-    } else {
-        int r0 = 0;
-        for (; r0 + 16 <= B; r0 += 16) {                   // 16 rows in flight at a time, added in row order
-            float x[16][VN];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) load_vec<T>(in + (int64_t)(r0 + r) * d, x[r]);
-#pragma unroll
-            for (int r = 0; r < 16; ++r)
+            for (int r = 0; r < BC; ++r)
 #pragma unroll
                 for (int e = 0; e < VN; ++e) s[e] = s[e] + x[r][e];
-        }
-        float x[VN];
-        for (int r = r0; r < B; ++r) {
-            load_vec<T>(in + (int64_t)r * d, x);
+        } else {
+            int r0 = 0;
+            for (; r0 + 16 <= B; r0 += 16) {                   // 16 rows in flight at a time, added in row order
+                float x[16][VN];
 #pragma unroll
-            for (int e = 0; e < VN; ++e) s[e] = s[e] + x[e];
+                for (int r = 0; r < 16; ++r) load_vec<T>(in + (int64_t)(r0 + r) * d, x[r]);
+#pragma unroll
+                for (int r = 0; r < 16; ++r)
+#pragma unroll
+                    for (int e = 0; e < VN; ++e) s[e] = s[e] + x[r][e];
+            }
+            float x[VN];
+            for (int r = r0; r < B; ++r) {
+                load_vec<T>(in + (int64_t)r * d, x);
+#pragma unroll
+                for (int e = 0; e < VN; ++e) s[e] = s[e] + x[e];
+            }
+        }
+        const float Bf = (float)B;
+#pragma unroll
+        for (int e = 0; e < VN; ++e) s[e] = __fdiv_rn(s[e], Bf);
+        store_vec<T>(static_cast<T *>(a.out[blockIdx.y]) + t * (int64_t)d + cv * VN, s);
+    }
+    if constexpr (TWO) {
+#pragma unroll
+        for (int e = 0; e < VN; ++e) lvl[threadIdx.x * VN + e] = to_f(from_f<T>(s[e]));   // what was stored, as fp32
+        __syncthreads();
+        const int tpw = 256 / vpr;                         // output tokens of this workgroup: tpw / B whole groups
+        const int t2l = threadIdx.x / vpr;                 // group this thread sums (threads beyond the groups idle)
+        const int64_t first = (int64_t)blockIdx.x * tpw;   // the workgroup's first output token: a multiple of B
+        if (t2l < tpw / B && first + (int64_t)(t2l + 1) * B <= n_out_total) {
+            float u[VN];
+#pragma unroll
+            for (int e = 0; e < VN; ++e) u[e] = 0.f;
+            for (int r = 0; r < B; ++r)
+#pragma unroll
+                for (int e = 0; e < VN; ++e) u[e] = u[e] + lvl[((t2l * B + r) * vpr + cv) * VN + e];
+            const float Bf = (float)B;
+#pragma unroll
+            for (int e = 0; e < VN; ++e) u[e] = __fdiv_rn(u[e], Bf);
+            store_vec<T>(static_cast<T *>(a.out2[blockIdx.y]) + (first / B + t2l) * (int64_t)d + cv * VN, u);
         }
     }
-    const float Bf = (float)B;
-#pragma unroll
-    for (int e = 0; e < VN; ++e) s[e] = __fdiv_rn(s[e], Bf);
-    store_vec<T>(static_cast<T *>(a.out[blockIdx.y]) + t * (int64_t)d + cv * VN, s);
 }
 
 hipError_t launch_pool(const Plan &p, const void *Q, const void *K, const void *V, void *ws, bool q_too,
                        hipStream_t s) {
     const void *src[3] = {Q, K, V};
     char *w = static_cast<char *>(ws);
+    const int vn = 16 / p.elt;
+    // levels 1 and 2 in one launch where a workgroup's 256 / (d / vn) level-1 tokens are whole groups of B
+    const bool two = p.L >= 2 && p.elt == 2 && p.B == 16 && (256 / (p.d / vn)) % p.B == 0;
     for (int l = 1; l <= p.L; ++l) {
+        if (two && l == 2) continue;
         PoolArgs a;
         int cnt = 0;
         for (int x = q_too ? 0 : 1; x < 3; ++x, ++cnt) {
             a.in[cnt] = (l == 1) ? src[x] : (const void *)(w + p.pyr_off[x][l - 1]);
             a.out[cnt] = w + p.pyr_off[x][l];
+            a.out2[cnt] = (two && l == 1) ? (void *)(w + p.pyr_off[x][2]) : nullptr;
         }
         const int64_t n_out_total = (int64_t)p.bh * p.n[l];
-        const int vn = 16 / p.elt;
         const int64_t threads = n_out_total * (p.d / vn);
         dim3 grid((unsigned)((threads + 255) / 256), cnt);
-        if (p.elt == 4) pool_kernel<float, 0><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
-        else if (p.B == 16) pool_kernel<bf16_t, 16><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
-        else                pool_kernel<bf16_t, 0><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        if (p.elt == 4) pool_kernel<float, 0, false><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else if (two && l == 1) pool_kernel<bf16_t, 16, true><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else if (p.B == 16) pool_kernel<bf16_t, 16, false><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else                pool_kernel<bf16_t, 0, false><<<grid, 256, 0, s>>>(a, n_out_total, p.d, p.B);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -249,13 +281,14 @@ hipError_t launch_qknorm_rope_pool(const Plan &p, const void *Qpre, const void *
         for (int x = (l == 1) ? 2 : 0; x < 3; ++x, ++cnt) {    // level 1 of Q and K is already there
             a.in[cnt] = (l == 1) ? src[x] : (const void *)(w + p.pyr_off[x][l - 1]);
             a.out[cnt] = w + p.pyr_off[x][l];
+            a.out2[cnt] = nullptr;
         }
         const int64_t n_out_total = (int64_t)p.bh * p.n[l];
         const int64_t th = n_out_total * (p.d / vn);
         dim3 pg((unsigned)((th + 255) / 256), cnt);
-        if (p.elt == 4) pool_kernel<float, 0><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
-        else if (p.B == 16) pool_kernel<bf16_t, 16><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
-        else                pool_kernel<bf16_t, 0><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        if (p.elt == 4) pool_kernel<float, 0, false><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else if (p.B == 16) pool_kernel<bf16_t, 16, false><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
+        else                pool_kernel<bf16_t, 0, false><<<pg, 256, 0, s>>>(a, n_out_total, p.d, p.B);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
     }

@@ -375,7 +375,13 @@ static llsa_status forward_impl(const llsa_plan_t *plan, const void *Q, const vo
     {
         StageScope sc(kSelect, call, s);
         char *idx = reinterpret_cast<char *>(indices);
-        for (int l = p.L; l >= 1; --l) {
+        int l = p.L;
+        if (select_top_fused(p)) {                          // levels L and L-1 in one launch
+            LLSA_TRY(launch_select_fast(p, p.L - 1, workspace, nullptr, reinterpret_cast<int32_t *>(idx + p.idx_off[p.L - 2]), s,
+                                        reinterpret_cast<int32_t *>(idx + p.idx_off[p.L - 1])));
+            l = p.L - 2;
+        }
+        for (; l >= 1; --l) {
             const int32_t *parent = (l < p.L) ? reinterpret_cast<const int32_t *>(idx + p.idx_off[l]) : nullptr;
             LLSA_TRY(launch_select(p, l, workspace, parent, reinterpret_cast<int32_t *>(idx + p.idx_off[l - 1]), s));
         }

@@ -80,7 +80,10 @@ hipError_t launch_reorder(int64_t bh, int64_t N, int row_bytes, int bits, int in
 
 // ---- fast selection (bf16, B = 16 / 32 / 64, K <= 64; any number of candidates, 256 at a time) ----
 bool select_fast_ok(const Plan &p, int l);
-hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s);
+// top_out != null: l = L - 1 and the launch also does level L, writing I^(L-1) to top_out (allowed if select_top_fused)
+hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s,
+                              int32_t *top_out = nullptr);
+bool select_top_fused(const Plan &p);
 
 // ---- bf16 MFMA kernels (B = 16 / 32 / 64, d = 64 or 128, N % 64 == 0) ----
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);

@@ -19,12 +19,23 @@ __device__ __forceinline__ void unpack8(u32x4 w, float *f) {
     }
 }
 
-// MC = candidates per lane (8: up to 128 candidates, 16: up to 256); KW = winners per lane (K <= 16 KW)
-template <int D, int MC, int KW>
+// The coarsest level's selection for kernels that run the level below it in the same launch (TOP).
+struct TopLevel {
+    const uint16_t *Q, *K;       // Q^(L), K^(L): [bh, n, D]
+    int32_t *out;                // I^(L-1): [bh, n, Kp]
+    int n;                       // tokens of level L per head (<= 64)
+};
+
+// MC = candidates per lane (8: up to 128 candidates, 16: up to 256); KW = winners per lane (K <= 16 KW).
+// TOP: this launch is level L-1 and also does level L (Alg. 1's first selection step, dense over the n_L <= 64
+// coarsest tokens): every workgroup scores the level-L token above its 16 queries against all level-L keys on its
+// first wave (same fp32 multiply-add chain, same tie rule), which gives the row of I^(L-1) it needs as `parent`; the
+// workgroup at the start of that row's B queries also writes it out.  One launch less on a latency-bound path.
+template <int D, int MC, int KW, bool TOP>
 __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__restrict__ Ql, const uint16_t *__restrict__ Kl,
                                                            int64_t n_l, const int32_t *__restrict__ parent, int Kp,
                                                            int Kout, int32_t *__restrict__ out, int C, int64_t nblk,
-                                                           int lb) {
+                                                           int lb, TopLevel top) {
     constexpr int STRIDE = 2 * D + 16;                      // bytes per staged row: keeps 16-byte reads conflict-free
     constexpr int CH = D / 8;                               // 16-byte chunks per row
     __shared__ __attribute__((aligned(16))) char kc[16 * MC * STRIDE];
@@ -37,6 +48,45 @@ __global__ void __launch_bounds__(256) select_fast_kernel(const uint16_t *__rest
     // B children each are the candidates
     const int Bm1 = (1 << lb) - 1;
     const int32_t *prow = parent ? parent + (bh * (n_l >> lb) + (r >> (lb - 4))) * Kp : nullptr;
+    if constexpr (TOP) {
+        __shared__ int32_t prow_sh[16];
+        if (tid < 64) {
+            const int64_t q = r >> (lb - 4);                 // the level-L token above this query block
+            float sc = -INFINITY;
+            if (tid < top.n) {
+                const uint16_t *qrow = top.Q + (bh * top.n + q) * D, *krow = top.K + (bh * top.n + tid) * D;
+                sc = 0.f;
+                for (int ch = 0; ch < CH; ++ch) {
+                    float qf[8], kf[8];
+                    unpack8(*reinterpret_cast<const u32x4 *>(qrow + ch * 8), qf);
+                    unpack8(*reinterpret_cast<const u32x4 *>(krow + ch * 8), kf);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) sc = __builtin_fmaf(qf[e], kf[e], sc);
+                }
+            }
+            int won = 0x7fffffff;                            // lane k: the k-th winner's key id
+            for (int k = 0; k < Kp; ++k) {
+                float bs = sc;
+                int bp = tid;
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) {
+                    const float os = __shfl_xor(bs, o, 64);
+                    const int op = __shfl_xor(bp, o, 64);
+                    if (os > bs || (os == bs && op < bp)) { bs = os; bp = op; }
+                }
+                if (bp == tid) sc = -INFINITY;
+                if (tid == k) won = bp;
+            }
+            int rank = 0;                                    // rows are stored in ascending id order
+            for (int k = 0; k < Kp; ++k) rank += (__shfl(won, k, 64) < won) ? 1 : 0;
+            if (tid < Kp) {
+                prow_sh[rank] = won;
+                if ((r & ((1 << (lb - 4)) - 1)) == 0) top.out[(bh * top.n + q) * Kp + rank] = won;
+            }
+        }
+        __syncthreads();
+        prow = prow_sh;
+    }
 
     // stage the candidate rows (16-byte chunks, coalesced within a row) and the query rows
     for (int c = tid; c < C * CH; c += 256) {
@@ -233,7 +283,14 @@ bool select_fast_ok(const Plan &p, int l) {
            (l == p.L || p.n[l] % 16 == 0);
 }
 
-hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s) {
+// Can level L be done inside level L-1's launch?
+bool select_top_fused(const Plan &p) {
+    if (p.L < 2 || p.desc.kernel_path != 0 || !select_fast_ok(p, p.L) || !select_fast_ok(p, p.L - 1)) return false;
+    return p.n[p.L] <= 64 && p.Kl[p.L - 1] <= 16 && p.Kl[p.L - 1] * p.B <= 256;
+}
+
+hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_t *parent, int32_t *out, hipStream_t s,
+                              int32_t *top_out) {
     const char *w = static_cast<const char *>(ws);
     const bool top = (l == p.L);
     const int64_t nblk = (p.n[l] + 15) / 16;
@@ -243,7 +300,24 @@ hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_
     dim3 grid((unsigned)(p.bh * nblk));
     const int C = top ? (int)p.n[l] : p.Kl[l] * p.B;
     const bool wide = Kout > 16;                            // up to 4 winners per lane instead of one
+    TopLevel tl = {nullptr, nullptr, nullptr, 0};
 #define LLSA_SEL(kernel, ...) kernel<<<grid, 256, 0, s>>>(__VA_ARGS__)
+    if (top_out) {                                          // level L-1 with level L inside (select_top_fused)
+        tl.Q = (const uint16_t *)(w + p.pyr_off[0][p.L]);
+        tl.K = (const uint16_t *)(w + p.pyr_off[1][p.L]);
+        tl.out = top_out;
+        tl.n = (int)p.n[p.L];
+        if (p.d == 64) {
+            if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<64, 8, 1, true>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+            else if (!wide) LLSA_SEL((select_fast_kernel<64, 16, 1, true>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+            else LLSA_SEL((select_fast_kernel<64, 16, 4, true>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+        } else {
+            if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<128, 8, 1, true>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+            else if (!wide) LLSA_SEL((select_fast_kernel<128, 16, 1, true>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+            else LLSA_SEL((select_fast_kernel<128, 16, 4, true>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+        }
+        return hipGetLastError();
+    }
     if (C > 256) {
         if (p.d == 64 && !wide) LLSA_SEL((select_dense_kernel<64, 1>), Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
         else if (p.d == 64) LLSA_SEL((select_dense_kernel<64, 4>), Ql, Kl, p.n[l], par, Kp, C, Kout, out, nblk, p.lb);
@@ -252,13 +326,13 @@ hipError_t launch_select_fast(const Plan &p, int l, const void *ws, const int32_
         return hipGetLastError();
     }
     if (p.d == 64) {
-        if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<64, 8, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
-        else if (!wide) LLSA_SEL((select_fast_kernel<64, 16, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
-        else LLSA_SEL((select_fast_kernel<64, 16, 4>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<64, 8, 1, false>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+        else if (!wide) LLSA_SEL((select_fast_kernel<64, 16, 1, false>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+        else LLSA_SEL((select_fast_kernel<64, 16, 4, false>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
     } else {
-        if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<128, 8, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
-        else if (!wide) LLSA_SEL((select_fast_kernel<128, 16, 1>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
-        else LLSA_SEL((select_fast_kernel<128, 16, 4>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb);
+        if (C <= 128 && !wide) LLSA_SEL((select_fast_kernel<128, 8, 1, false>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+        else if (!wide) LLSA_SEL((select_fast_kernel<128, 16, 1, false>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
+        else LLSA_SEL((select_fast_kernel<128, 16, 4, false>), Ql, Kl, p.n[l], par, Kp, Kout, out, C, nblk, p.lb, tl);
     }
 #undef LLSA_SEL
     return hipGetLastError();

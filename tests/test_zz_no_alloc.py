@@ -58,3 +58,40 @@ def test_forward_static_refuses_a_plan_beyond_the_static_workspace():
     st = lib.llsa_forward_static(plan._h, _vp(one), _vp(one), _vp(one), _vp(one), _vp(one), _vp(one), None)
     assert st == 4
     assert b"static" in lib.llsa_status_string(st)
+
+
+def test_forward_static_replays_from_a_hip_graph():
+    """What the entry point is for: captured into a HIP graph (after one eager call, which looks the static array's
+    address up), every replay -- with eager work of the program and synchronisations between the replays -- gives the
+    eager result bit for bit."""
+    cfg = CASES[1]
+    x = H.make_inputs(cfg, 4250)
+    Q, K, V = (H.to_dev(x[n], cfg) for n in ("Q", "K", "V"))
+    plan = H.make_plan(cfg)
+    O = torch.empty_like(Q)
+    LSE = torch.empty(cfg["batch"], cfg["heads"], cfg["N"], dtype=torch.float32, device="cuda")
+    idx = plan.alloc_indices()
+    llsa.forward_static(plan, Q, K, V, O, LSE, idx)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (O, LSE, idx)]
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            llsa.forward_static(plan, Q, K, V, O, LSE, idx)
+    torch.cuda.current_stream().wait_stream(side)
+    other = H.make_plan(CASES[0])                                  # another problem uses the shared array in between
+    xo = H.make_inputs(CASES[0], 4251)
+    Qo, Ko, Vo = (H.to_dev(xo[n], CASES[0]) for n in ("Q", "K", "V"))
+    Oo, LSEo, idxo = torch.empty_like(Qo), torch.empty(1, 4, 16384, dtype=torch.float32, device="cuda"), other.alloc_indices()
+    for rep in range(3):
+        O.zero_()
+        LSE.zero_()
+        idx.fill_(-1)
+        llsa.forward_static(other, Qo, Ko, Vo, Oo, LSEo, idxo)     # overwrites the static workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, got, want in zip(("O", "LSE", "indices"), (O, LSE, idx), ref):
+            assert torch.equal(got, want), f"replay {rep}: {name} differs from the eager result"
