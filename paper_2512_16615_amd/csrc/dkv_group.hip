@@ -6,9 +6,11 @@
 // the key-major tile loop over the 8 query tiles of R against R's coarse key blocks:
 //   S = Q K^T, dP = dO V^T (lane: 4 queries x 1 key) -> P, dS -> dV^T += dO^T P, dK^T += Q^T dS.
 // That yields, per (query group, coarse block of its list), the block's gradient restricted to the group's
-// queries: a fp32 partial of 2 x 16 x d values.  Two kernels produce the partials:
+// queries: a fp32 partial of 2 x 16 x d values.  Three kernels produce the partials:
 //   dkv_group_kernel: one R per workgroup; a wave takes NB list blocks at a time (d = 64: 4 waves x 2 blocks fed
 //     from one LDS read of each tile; d = 128: 8 waves x 1 block) of the levels it is given;
+//   dkv_chain_kernel: level 1 with 8 listed blocks at d = 64.  The same tile loop, but a workgroup walks several
+//     consecutive R and a key block listed by a run of them keeps its sums in registers: one partial per run;
 //   dkv_upper_kernel: levels >= 2 only.  The 16 level-1 blocks under one level-2 query block list the same
 //     key blocks at every level >= 2, so a workgroup of 8 waves walks G of them (G divides 16; the next one's
 //     rows are prefetched into registers) and keeps its accumulators in registers meanwhile: every wave owns
@@ -44,6 +46,7 @@ struct GroupArgs {
     int64_t N, NR;                                      // NR = level-1 query blocks per head
     int lev_end;                                        // levels below lev_end are processed (from 1, or from 2 in the upper kernel)
     int G;                                              // level-1 query blocks per workgroup (upper kernel)
+    int GC;                                             // level-1 query blocks a workgroup of the chain kernel walks
     int nbs, nbd;                                       // upper kernel: listed blocks of its sparse levels / of the dense level
     int sparse_begin, do_dense;                         // upper kernel: first sparse block of this launch; does it take the dense one
     float sc2, scale;
@@ -222,6 +225,94 @@ __global__ void __launch_bounds__(64 * NW) dkv_group_kernel(LevelTable t, GroupA
     }
 }
 
+// Level 1 alone, rows of I^(1) with exactly NW * NB entries.  Neighbouring level-1 query blocks list mostly the same
+// level-1 key blocks (for spatially smooth inputs a block stays listed over many consecutive rows), and a partial per
+// (query block, listed block) then carries the same key block's sums to memory again and again.  Here a workgroup
+// walks GC consecutive level-1 query blocks and keeps one listed block per register slot, as dkv_group_kernel does
+// for a single query block.  From one query block R to the next, a slot whose key block is listed again goes on
+// accumulating; a slot whose block is not listed by R + 1 writes its partial to the place of (R, the block's
+// position in R's row) and takes one of the blocks that are new in R + 1 (both rows have NW * NB distinct entries,
+// so as many slots come free as blocks are new).  A partial therefore covers a run of consecutive query blocks of
+// one chain that all list the key block, and sits where the last of them would have put its own; the gather skips
+// a lister whose successor in the same chain lists the block too.  Same arithmetic per tile, fewer partials.
+template <int D, int NW, int NB>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2))) dkv_chain_kernel(LevelTable t, GroupArgs a) {
+    using S = GShape<D>;
+    constexpr int SL = NW * NB;
+    __shared__ __attribute__((aligned(16))) char qs[256 * S::ROWB];
+    __shared__ __attribute__((aligned(16))) char gs[256 * S::ROWB];
+    __shared__ __attribute__((aligned(16))) float st[512];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 4;
+    const int64_t per_head = a.NR / a.GC;
+    const int64_t grp = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int64_t bh = grp / per_head, R0 = (grp % per_head) * a.GC;
+    const TileOffsets<D> o = tile_offsets<D>(lane);
+    const int32_t *I1 = t.I[1] + (bh * a.NR + R0) * SL;               // I^(1) has one row per level-1 query block
+    const char *K1 = static_cast<const char *>(t.K[1]) + bh * t.n[1] * D * 2;
+    const char *V1 = static_cast<const char *>(t.V[1]) + bh * t.n[1] * D * 2;
+    const float bias2 = t.bias[1] * kLog2e;
+    float *slab1 = a.slab + a.lvl_off[1] + (bh * a.NR + R0) * SL * S::UNIT;
+
+    int sblk = -1, spos = 0;                                          // lane s < SL: the block slot s holds, its place in the row
+    BlockAcc<D> blk[NB];                                              // this wave's slots NB * wave ...
+    for (int r = 0; r < a.GC; ++r) {
+        StageRegs<D, 64 * NW> sr;
+        stage_load<D, 64 * NW>(sr, a, bh * a.N + (R0 + r) * 256, tid);   // in flight during the bookkeeping below
+        const int nb = lane < SL ? I1[r * SL + lane] : -1;            // lane p: entry p of this query block's row
+        if (r == 0) {
+            sblk = nb;
+            spos = lane;
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int64_t id = __builtin_amdgcn_readlane(nb, NB * wave + b);
+                blk[b].load(K1 + id * 16 * D * 2, V1 + id * 16 * D * 2, 16, bias2, lane);
+                blk[b].clear();
+            }
+        } else {
+            bool keep = false, fresh = lane < SL;
+            int npos = 0;
+#pragma unroll
+            for (int x = 0; x < SL; ++x) {
+                if (sblk == __builtin_amdgcn_readlane(nb, x)) { keep = true; npos = x; }
+                if (nb == __builtin_amdgcn_readlane(sblk, x)) fresh = false;
+            }
+            const uint64_t kept = __ballot(keep), freed = __ballot(lane < SL && !keep), news = __ballot(fresh);
+            // the k-th slot that comes free takes the k-th new entry of the row
+            const int k = __popcll(freed & ((1ull << lane) - 1));
+            uint64_t m = news;
+#pragma unroll
+            for (int x = 0; x < SL; ++x) m = (x < k) ? (m & (m - 1)) : m;
+            const int src = m ? (int)__builtin_ctzll(m) : 0;
+            const int nid = __shfl(nb, src, 64);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int s = NB * wave + b;
+                if (!((kept >> s) & 1)) {                             // wave-uniform
+                    const int oldpos = __builtin_amdgcn_readlane(spos, s);
+                    store_partial<D>(slab1 + ((int64_t)(r - 1) * SL + oldpos) * S::UNIT, blk[b], a.scale, lane);
+                    const int64_t id = __builtin_amdgcn_readlane(nid, s);
+                    blk[b].load(K1 + id * 16 * D * 2, V1 + id * 16 * D * 2, 16, bias2, lane);
+                    blk[b].clear();
+                }
+            }
+            sblk = keep ? sblk : nid;
+            spos = keep ? npos : src;
+        }
+        __syncthreads();                                              // everyone is done with the previous rows
+        stage_store<D, 64 * NW>(sr, qs, gs, st, tid);
+        __syncthreads();
+        for (int u = 0; u < 8; ++u) group_tile<D, NB>(qs, gs, st, u, o, blk, a.sc2, g);
+    }
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int pos = __builtin_amdgcn_readlane(spos, NB * wave + b);
+        store_partial<D>(slab1 + ((int64_t)(a.GC - 1) * SL + pos) * S::UNIT, blk[b], a.scale, lane);
+    }
+}
+
 // SS = sparse blocks a wave owns in one launch (blocks sparse_begin + wave, + 8, ...): a launch covers 8 SS of them;
 // DENSE: may this instantiation take the shared dense block
 template <int D, int SS, bool DENSE>
@@ -336,6 +427,7 @@ struct GatherArgs {
     float *dstK, *dstV;          // [bh, n_l, D]
     int64_t cnt, n_l, nkb, rows; // listers per head, tokens, key blocks per head, rows of I^(l)
     int nblk, Kl, dense;
+    int chain;                   // > 1: partials come from the chain kernel, which walked `chain` consecutive listers
 };
 template <int D>
 __global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
@@ -364,11 +456,18 @@ __global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
                 const int32_t *row = a.I + (bh * a.rows + r) * a.Kl;
                 int pos = 0;
                 for (int x = 0; x < a.Kl; ++x) pos += (row[x] < (int32_t)j) ? 1 : 0;   // rows are ascending
-                unit[tid] = ((bh * a.cnt + r) * a.nblk + pos) * U4;
+                int64_t un = ((bh * a.cnt + r) * a.nblk + pos) * U4;
+                if (a.chain > 1 && r % a.chain != a.chain - 1) {                  // carried on by the next lister of the chain?
+                    bool cont = false;
+                    for (int x = 0; x < a.Kl; ++x) cont |= row[a.Kl + x] == (int32_t)j;
+                    if (cont) un = -1;
+                }
+                unit[tid] = un;
             }
             __syncthreads();
 #pragma unroll 4
             for (int32_t e = 0; e < m; ++e) {
+                if (unit[e] < 0) continue;                                // same for every thread
                 const f32x4 *p = part + unit[e];
 #pragma unroll
                 for (int x = 0; x < PER; ++x) { k[x] += p[tid + 256 * x]; v[x] += p[H4 + tid + 256 * x]; }
@@ -420,6 +519,23 @@ static int upper_G(const Plan &p) {
     int G = 16;                                             // divides 16, so a group never straddles a level-2 query block
     while (G > 1 && (NR % G != 0 || (int64_t)p.bh * (NR / G) < 256)) G >>= 1;  // one workgroup of 8 waves per CU
     return G;
+}
+
+// Level-1 query blocks one workgroup of the chain kernel walks (1: the plain group kernel takes level 1).
+// d = 64 with rows of 8 level-1 blocks, level 1 sparse and the only level the kernel is given.
+#ifndef LLSA_CHAIN
+#define LLSA_CHAIN 8
+#endif
+#ifndef LLSA_CHAIN_WG
+#define LLSA_CHAIN_WG 512
+#endif
+static int chain_len(const Plan &p) {
+    if (p.d != 64 || p.L < 2 || p.Kl[1] != 8) return 1;
+    if (upper_G(p) == 0 && dkv_group_top(p) > 1) return 1;
+    const int64_t NR = p.N / 256;
+    int GC = LLSA_CHAIN;
+    while (GC > 1 && (NR % GC != 0 || (int64_t)p.bh * (NR / GC) < LLSA_CHAIN_WG)) GC >>= 1;   // two workgroups per CU
+    return GC;
 }
 
 // partial-slab layout: level 1 has one partial per (level-1 query block, list position), levels >= 2 one per
@@ -493,6 +609,7 @@ static hipError_t finish_level(const Plan &p, const LevelTable &t, const GroupAr
     ga.dstV = (float *)(w + p.dVacc_off[l]);
     ga.cnt = cnt; ga.n_l = p.n[l]; ga.nkb = (p.n[l] + 15) / 16; ga.rows = dense ? 0 : p.n[l + 1];
     ga.nblk = a.nblk[l]; ga.Kl = dense ? 0 : p.Kl[l];
+    ga.chain = l == 1 ? a.GC : 1;
     const dim3 grid((unsigned)(p.bh * ga.nkb));
     if (p.d == 64) dkv_gather_kernel<64><<<grid, 256, 0, s>>>(ga);
     else dkv_gather_kernel<128><<<grid, 256, 0, s>>>(ga);
@@ -500,6 +617,10 @@ static hipError_t finish_level(const Plan &p, const LevelTable &t, const GroupAr
 }
 
 static hipError_t launch_group_kernel(const Plan &p, const LevelTable &t, const GroupArgs &a, hipStream_t s) {
+    if (a.GC > 1) {
+        dkv_chain_kernel<64, 4, 2><<<dim3((unsigned)(p.bh * (a.NR / a.GC))), 256, 0, s>>>(t, a);
+        return hipGetLastError();
+    }
     const dim3 grid((unsigned)(p.bh * a.NR));
     if (p.d == 64) dkv_group_kernel<64, 4, 2><<<grid, 256, 0, s>>>(t, a);
     else dkv_group_kernel<128, 8, 1><<<grid, 512, 0, s>>>(t, a);
@@ -519,6 +640,7 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
     a.sc2 = p.scale * kLog2e; a.scale = p.scale;
     slab_layout(p, a.lvl_off, a.nblk, groups);
     a.G = G;
+    a.GC = chain_len(p);
     upper_blocks(p, &a.nbs, &a.nbd);
     a.sparse_begin = 0;
     a.do_dense = 0;

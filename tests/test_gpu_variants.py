@@ -118,3 +118,57 @@ def test_layer_on_reordered_tokens():
     gpu = H.gpu_forward_backward(cfg, nested)
     H.properties_all_heads(cfg, gpu, nested)
     H.sampled_parity(cfg, gpu, nested, heads=[(0, 1)], n_row_chunks=3, full_backward_head=(0, 1))
+
+
+def test_level1_partials_carried_across_query_blocks():
+    """Level-1 dK/dV where one workgroup walks 8 consecutive level-1 query blocks and carries a key block's sums in
+    registers while the following query blocks keep listing it (64 heads x 64 level-1 query blocks: enough work for
+    that kernel to be chosen).  Lists are forced (Alg. 1 allows any valid rows) so that the cases are certain to
+    occur: alternating disjoint rows (a block dropped and taken up again inside one walk), a window sliding by one
+    block per row, identical rows, rows whose new blocks sort before the ones kept, random rows."""
+    import numpy as np
+    import torch
+    from oracle import llsa_oracle as orc
+    from paper_2512_16615_amd import llsa
+    cfg = dict(BASE, name="n16384_forced_lists", N=16384, batch=4, heads=16, L=3)
+    g = H.geometry(cfg)
+    two = H.make_inputs_parallel(dict(cfg, batch=1, heads=2), 0xC4A1)             # two distinct heads, repeated
+    x = {n: np.ascontiguousarray(np.tile(v, (4, 8, 1, 1))) for n, v in two.items()}
+    plan = H.make_plan(cfg)
+    Q, K, V, dO = (H.to_dev(x[n], cfg) for n in ("Q", "K", "V", "dO"))
+    ws, idx = plan.alloc_workspace(True), plan.alloc_indices()
+    llsa.pool(plan, Q, K, V, ws)
+
+    rng = np.random.default_rng(77)
+    def rows(n_rows, n_keys, k):
+        return np.stack([np.sort(rng.choice(n_keys, k, replace=False)) for _ in range(n_rows)]).astype(np.int32)
+    A, Bs = np.arange(8), np.arange(8, 16)
+    I1 = []
+    for h in range(2):
+        r = rows(g.n(2), g.n(2), 8)
+        if h == 0:
+            r[0:8] = np.stack([A, Bs, A, Bs, A, A, Bs, Bs])
+            r[8:16] = np.stack([np.arange(i, i + 8) for i in range(8)])
+            r[16:24] = np.array([3, 9, 17, 20, 33, 41, 50, 63])
+            r[24:32] = np.stack([np.arange(40 - i, 48 - i) for i in range(8)])
+        I1.append(r)
+    I = [[rows(g.n(1), g.n(1), 8), I1[h], np.tile(np.arange(4, dtype=np.int32), (g.n(3), 1))] for h in range(2)]
+    for l in range(3):
+        lev = torch.from_numpy(np.stack([I[h][l] for h in range(2)])).cuda().repeat(4, 8, 1, 1)
+        plan.level_indices(idx, l).copy_(lev)
+    O, LSE = llsa.attention(plan, Q, K, V, idx, ws)
+    dQ, dK, dV = llsa.backward(plan, Q, K, V, O, LSE, idx, dO, ws)
+    torch.cuda.synchronize()
+    tol = H.TOL["bf16"]
+    for (b, h) in ((0, 0), (3, 15)):
+        Kp, Vp = orc.pyramid(x["K"][b, h], g, True), orc.pyramid(x["V"][b, h], g, True)
+        idx_cat = orc.cat_indices(I[h % 2])
+        o, lse = orc.attn_fwd(x["Q"][b, h], orc.cat_pyramid(Kp), orc.cat_pyramid(Vp), idx_cat, g, 3)
+        H.check_close(f"O{(b, h)}", H.f32(O[b, h]), o, tol["out"], tol["ulp"])
+        H.check_close(f"LSE{(b, h)}", H.f32(LSE[b, h]), lse, tol["lse"])
+        bw = H.oracle_backward_threads(x["Q"][b, h], Kp, Vp, idx_cat, x["dO"][b, h], g, 3)
+        for name, got in (("dQ", dQ), ("dK", dK), ("dV", dV)):
+            H.check_close(f"{name}{(b, h)}", H.f32(got[b, h]), bw[name], tol["out"], tol["ulp"])
+    # all copies of a head get bit-identical gradients (different workgroups, same arithmetic)
+    for t_ in (dK, dV):
+        assert torch.equal(t_[0, 0], t_[3, 14]) and torch.equal(t_[0, 1], t_[2, 7])
