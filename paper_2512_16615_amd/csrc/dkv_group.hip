@@ -628,7 +628,8 @@ static hipError_t launch_group_kernel(const Plan &p, const LevelTable &t, const 
 }
 
 hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
-                            const float *D, void *ws, hipStream_t s, hipEvent_t lists) {
+                            const float *D, void *ws, hipStream_t s, hipEvent_t lists, hipStream_t side,
+                            hipEvent_t upper_done) {
     char *w = static_cast<char *>(ws);
     const int64_t NR = p.N / 256;
     const int top = dkv_group_top(p), G = upper_G(p);
@@ -661,10 +662,19 @@ hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, c
             GRP_TRY(hipGetLastError());
         }
     }
+    // With a side stream (the one the lists are made on), the small reductions and gathers of levels >= 2 follow the
+    // lists there, beside the level-1 kernel, and `lists` is recorded again behind them.
+    const bool split = G && side && lists && upper_done && top >= 2;
+    if (split) {
+        GRP_TRY(hipEventRecord(upper_done, s));
+        GRP_TRY(hipStreamWaitEvent(side, upper_done, 0));
+        for (int l = top; l >= 2; --l) GRP_TRY(finish_level(p, t, a, l, groups[l], w, side));
+        GRP_TRY(hipEventRecord(lists, side));
+    }
     a.lev_end = G ? 2 : top + 1;
     GRP_TRY(launch_group_kernel(p, t, a, s));
     if (lists) GRP_TRY(hipStreamWaitEvent(s, lists, 0));
-    for (int l = top; l >= 1; --l) GRP_TRY(finish_level(p, t, a, l, groups[l], w, s));
+    for (int l = split ? 1 : top; l >= 1; --l) GRP_TRY(finish_level(p, t, a, l, groups[l], w, s));
     return hipSuccess;
 }
 

@@ -183,7 +183,7 @@ struct Aux {
     bool tried = false, ok = false;
     int device = -1;
     hipStream_t side = nullptr;
-    hipEvent_t ev[2] = {nullptr, nullptr};   // fork (the side stream may start), lists ready (join)
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // fork (the side stream may start), end of the side stream's work (lists ready; join), coarse partials written
 };
 
 struct llsa_plan_s {
@@ -204,7 +204,7 @@ static Aux *aux_for_call(const llsa_plan_s *plan, hipStream_t s) {
         a.tried = true;
         a.device = dev;
         bool ok = hipStreamCreateWithFlags(&a.side, hipStreamNonBlocking) == hipSuccess;
-        for (int i = 0; ok && i < 2; ++i) ok = hipEventCreateWithFlags(&a.ev[i], hipEventDisableTiming) == hipSuccess;
+        for (int i = 0; ok && i < 3; ++i) ok = hipEventCreateWithFlags(&a.ev[i], hipEventDisableTiming) == hipSuccess;
         a.ok = ok;
     }
     return (a.ok && a.device == dev) ? &a : nullptr;
@@ -439,7 +439,7 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     // and a level above their range is dense and has none), that is behind dQ, in the shadow of those kernels:
     // they are bound by LDS and leave wave slots and registers free, which dQ does not.  Otherwise it is beside dQ.
     const bool shadow = aux && p.group;
-    bool forked = false, lists_recorded = false, joined = false;
+    bool forked = false, joined = false;
     auto transpose = [&]() -> llsa_status {
         const int top_listed = p.Le < p.L ? p.Le : p.L - 1;    // highest level that has index lists in use
         if (aux) {
@@ -451,7 +451,6 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
         LLSA_TRY(launch_csc(p, top_listed, indices, workspace, side));
         if (aux) {
             LLSA_TRY(hipEventRecord(aux->ev[1], side));
-            lists_recorded = true;
         }
         return LLSA_OK;
     };
@@ -475,7 +474,8 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
             StageScope sc(kDkvCoarse, call, s);
             if (p.group) {                                  // levels above the grouped kernel's range first
                 for (int l = p.Le; l > dkv_group_top(p); --l) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
-                LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, shadow ? lists : nullptr));
+                LLSA_TRY(launch_dkv_group(p, t, Q, dO, LSE, D, workspace, s, shadow ? lists : nullptr, shadow ? side : nullptr,
+                                          shadow ? aux->ev[2] : nullptr));
                 if (shadow) joined = true;                  // the grouped launcher waits for the lists before its gathers
             } else for (int l = p.Le; l >= 1; --l) {
                 if (p.fast) LLSA_TRY(launch_dkv_mfma(p, t, l, Q, dO, LSE, D, workspace, dK, dV, s));
@@ -496,7 +496,8 @@ llsa_status llsa_backward(const llsa_plan_t *plan, const void *Q, const void *K,
     if (forked && !joined) {
         // A launch failed after the fork: still lead the auxiliary stream back into the caller's, so that a stream
         // capture in progress is not left with an unjoined branch.  Errors here cannot make the outcome worse.
-        if (!lists_recorded) (void)hipEventRecord(aux->ev[1], side);
+        // (recorded again even if it was before: the side stream may have been given more work since)
+        (void)hipEventRecord(aux->ev[1], side);
         (void)hipStreamWaitEvent(s, aux->ev[1], 0);
     }
     return st;

@@ -102,9 +102,12 @@ hipError_t launch_dkv_mfma(const Plan &p, const LevelTable &t, int l, const void
 int dkv_splits(const Plan &p, int l);    // workgroups sharing one key block's query list at level l
 // all coarse levels (dkv_group_top .. 1) at once, grouped by level-1 query block; fills the levels' fp32
 // gradients.  `lists` (or null): event after which the key-major lists are complete, recorded on another stream;
-// `s` waits for it behind the kernels that need no list, before the gathers.
+// `s` waits for it behind the kernels that need no list, before the gathers.  `side`, `upper_done` (or null): the
+// stream the lists are made on and a spare event; the reductions and gathers of levels >= 2 then run on `side` behind
+// the lists, beside the level-1 kernel, and `lists` is recorded once more behind them (so it still marks the end of `side`).
 hipError_t launch_dkv_group(const Plan &p, const LevelTable &t, const void *Q, const void *dO, const float *LSE,
-                            const float *D, void *ws, hipStream_t s, hipEvent_t lists);
+                            const float *D, void *ws, hipStream_t s, hipEvent_t lists, hipStream_t side = nullptr,
+                            hipEvent_t upper_done = nullptr);
 void dkv_group_sizes(const Plan &p, size_t *slab_bytes, size_t *red_bytes);
 int dkv_group_top(const Plan &p);         // highest level the grouped kernel takes (the rest: split kernel)
 
