@@ -75,7 +75,8 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
     // (log2 units), so probabilities stay below 2^kLazy, which costs fp32 / bf16 no precision, and a tile's usual
     // cost is a lane-local maximum and one compare.  Scale, level weight and reference are folded into the one
     // multiply-add in front of the exponential.
-    auto softmax_pv = [&](auto bsel, f32x4 s0, f32x4 s1, int c0, int c1, float b0, float b1, const char *vt, auto vstride) {
+    auto softmax_pv = [&](auto bsel, f32x4 s0, f32x4 s1, int c0, int c1, float b0, float b1, const char *vt, auto vstride,
+                          auto joint) -> bf16x8 {
         constexpr int b = decltype(bsel)::value;
         constexpr int VS = decltype(vstride)::value;                  // bytes between the V tile's key rows
         f32x4 s[2] = {s0, s1};
@@ -110,10 +111,15 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
                 lsum[b] += s[h][r];
             }
         const bf16x8 pop = pack8(s[0], s[1]);
-        const char *base = vt + (4 * g + (i16 >> 2)) * VS + (i16 & 3) * 8;
+        if constexpr (decltype(joint)::value) {
+            return pop;                                               // the caller multiplies both blocks' P with one read of V
+        } else {
+            const char *base = vt + (4 * g + (i16 >> 2)) * VS + (i16 & 3) * 8;
 #pragma unroll
-        for (int n = 0; n < NT; ++n)
-            acc[b][n] = mfma16(lds_tr_pair(base + n * 32, base + 16 * VS + n * 32), pop, acc[b][n]);
+            for (int n = 0; n < NT; ++n)
+                acc[b][n] = mfma16(lds_tr_pair(base + n * 32, base + 16 * VS + n * 32), pop, acc[b][n]);
+            return pop;
+        }
     };
     using StrideA = std::integral_constant<int, STRIDE>;
     using StrideB = std::integral_constant<int, VSTRIDE>;
@@ -212,8 +218,19 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 #pragma unroll
                     for (int ks = 0; ks < KS; ++ks) s[b][h] = mfma16(kop[h][ks], qop[b][ks], s[b][h]);
                 }
-            softmax_pv(B0{}, s[0][0], s[0][1], cnt[0], cnt[1], bias2[0], bias2[1], vt, StrideA{});
-            if constexpr (NB > 1) softmax_pv(B1{}, s[NB - 1][0], s[NB - 1][1], cnt[0], cnt[1], bias2[0], bias2[1], vt, StrideA{});
+            if constexpr (NB > 1) {                                   // both blocks' P first, then one transposing read of V for both
+                const bf16x8 p0 = softmax_pv(B0{}, s[0][0], s[0][1], cnt[0], cnt[1], bias2[0], bias2[1], vt, StrideA{}, std::true_type{});
+                const bf16x8 p1 = softmax_pv(B1{}, s[NB - 1][0], s[NB - 1][1], cnt[0], cnt[1], bias2[0], bias2[1], vt, StrideA{}, std::true_type{});
+                const char *base = vt + (4 * g + (i16 >> 2)) * STRIDE + (i16 & 3) * 8;
+#pragma unroll
+                for (int n = 0; n < NT; ++n) {
+                    const bf16x8 vtr = lds_tr_pair(base + n * 32, base + 16 * STRIDE + n * 32);
+                    acc[0][n] = mfma16(vtr, p0, acc[0][n]);
+                    acc[NB - 1][n] = mfma16(vtr, p1, acc[NB - 1][n]);
+                }
+            } else {
+                softmax_pv(B0{}, s[0][0], s[0][1], cnt[0], cnt[1], bias2[0], bias2[1], vt, StrideA{}, std::false_type{});
+            }
         }
     }
 
@@ -265,7 +282,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
                     s[h] = mfma16(*reinterpret_cast<const bf16x8 *>(my_k + (h * 16 + i16) * STRIDE + g * 16 + ks * 64), qop[b][ks], s[h]);
             }
             const int c1 = (j0 + 1 < nb0) ? 16 : 0;                   // level-0 blocks are always full
-            softmax_pv(bsel, s[0], s[1], 16, c1, 0.f, 0.f, my_v, StrideB{});
+            softmax_pv(bsel, s[0], s[1], 16, c1, 0.f, 0.f, my_v, StrideB{}, std::false_type{});
         }
     };
     load_tile(0, 0);
