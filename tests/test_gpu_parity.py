@@ -238,16 +238,19 @@ def test_first_backward_under_capture_stays_on_one_stream():
             assert torch.equal(got, ref[name]), f"replay {rep}: {name}"
 
 
-def test_hip_graph_replays_match_eager():
+@pytest.mark.parametrize("heads,N,L", [(4, 4096, 2), (16, 16384, 3)])
+def test_hip_graph_replays_match_eager(heads, N, L):
     """The library never allocates or synchronises, so a forward+backward step can be captured in a HIP graph;
-    every replay (with eager work and synchronisations in between) must reproduce the eager results bit for bit."""
-    cfg = dict(name="graph", batch=1, heads=4, d=64, N=4096, B=16, K=8, L=2, dtype="bf16", kind="smooth")
+    every replay (with eager work and synchronisations in between) must reproduce the eager results bit for bit.
+    The larger shape has three coarse levels and enough level-1 query blocks for the kernel that carries sums across
+    query blocks; in both, small kernels of the backward run on the plan's auxiliary stream inside the capture."""
+    cfg = dict(name="graph", batch=1, heads=heads, d=64, N=N, B=16, K=8, L=L, dtype="bf16", kind="smooth")
     x = H.make_inputs(cfg, 31)
     plan = H.make_plan(cfg)
     Q, K, V, dO = (H.to_dev(x[n], cfg) for n in ("Q", "K", "V", "dO"))
     ws, idx = plan.alloc_workspace(True), plan.alloc_indices()
     O, dQ, dK, dV = (torch.empty_like(Q) for _ in range(4))
-    LSE = torch.empty(1, 4, 4096, dtype=torch.float32, device="cuda")
+    LSE = torch.empty(1, heads, N, dtype=torch.float32, device="cuda")
 
     def step():
         llsa.forward(plan, Q, K, V, O, LSE, idx, ws)
