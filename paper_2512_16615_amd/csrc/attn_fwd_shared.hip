@@ -31,28 +31,31 @@ __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) {
     return c.b;
 }
 
-// NB = fine query blocks per wave (1 or 2); a workgroup owns 8 * NB consecutive blocks, all siblings
-template <int D, int NB>
-__global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2))) attn_fwd_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q,
+// NB = fine query blocks per wave (1 or 2), NW = waves per workgroup (4 or 8); a workgroup owns NW * NB consecutive
+// blocks, all siblings
+template <int D, int NB, int NW = 8>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(D == 64 ? 4 : 2))) attn_fwd_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q,
                                                                uint16_t *__restrict__ O, float *__restrict__ LSE,
                                                                int64_t N, int64_t total_wgs) {
     constexpr int KS = D / 32, NT = D / 16, STRIDE = D * 2 + 32, PARTS = D / 8, TILE = 32 * STRIDE;
-    constexpr int RND = (2 * 32 * PARTS) / 512;         // staging rounds of the workgroup per shared tile (K and V)
+    constexpr int NTHR = 64 * NW;
+    constexpr int RND = (2 * 32 * PARTS) / NTHR;        // staging rounds of the workgroup per shared tile (K and V)
+    static_assert(RND == 1 || NTHR == 32 * PARTS, "with two rounds, round 0 is the K half and round 1 the V half");
     constexpr int VCH = D / 16, KPU = 64 / PARTS;       // private V staging of one wave (phase B)
     // Phase B: per wave a K tile (row-wise reads: rows 32 bytes apart in the banks) and a V tile (transposed reads only:
     // 16 bytes of padding do).  Phase A's two double-buffered [K | V] tiles live in the first 4 TILE bytes of the same
     // memory; a workgroup barrier separates the phases.
     constexpr int VSTRIDE = D * 2 + 16, VTILE = 32 * VSTRIDE;
-    __shared__ __attribute__((aligned(16))) char lds[8 * (TILE + VTILE)];
-    static_assert(4 * TILE <= 8 * (TILE + VTILE), "phase A's buffers must fit");
+    __shared__ __attribute__((aligned(16))) char lds[NW * (TILE + VTILE)];
+    static_assert(4 * TILE + 6 * 64 * 4 <= NW * (TILE + VTILE), "phase A's buffers and the block table must fit");
     auto sh = [&](int buf, int which) { return lds + (buf * 2 + which) * TILE; };
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int i16 = lane & 15, g = lane >> 4;
-    const int64_t groups = N / (128 * NB);                            // workgroups per head
+    const int64_t groups = N / (16 * NW * NB);                        // workgroups per head
     const int64_t wg = xcd_contiguous(blockIdx.x, total_wgs);
-    const int64_t bh = wg / groups, blk0 = (wg % groups) * (8 * NB);
+    const int64_t bh = wg / groups, blk0 = (wg % groups) * (NW * NB);
     const float sc2 = t.scale * kLog2e;
 
     bf16x8 qop[NB][KS];
@@ -153,7 +156,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
         unsigned s_off[RND];
 #pragma unroll
         for (int r = 0; r < RND; ++r) {
-            const int key0 = ((64 * wave + 512 * r) % (32 * PARTS)) / PARTS;   // the wave's first key row in round r
+            const int key0 = ((64 * wave + NTHR * r) % (32 * PARTS)) / PARTS;   // the wave's first key row in round r
             s_half[r] = key0 >> 4;
             s_off[r] = (unsigned)((((key0 & 15) + lane / PARTS) * D + (lane % PARTS) * 8) * 2);
         }
@@ -181,7 +184,7 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
         auto store_shared = [&](int buf) {
 #pragma unroll
             for (int r = 0; r < RND; ++r) {
-                const int cc = tid + 512 * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
+                const int cc = tid + NTHR * r, which = cc / (32 * PARTS), c = cc % (32 * PARTS);
                 *reinterpret_cast<u32x4 *>(sh(buf, which) + (c / PARTS) * STRIDE + (c % PARTS) * 16) = sreg[r];
             }
         };
@@ -309,10 +312,12 @@ __global__ void __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(D == 6
 
 hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                   hipStream_t s) {
-    if (p.d == 64 && (p.Kl[0] << (p.lb - 4)) <= 32) { // two query blocks per wave (measured faster than one): 16 per workgroup
-        const int64_t wgs = (int64_t)p.bh * (p.N / 256);
-        attn_fwd_shared_kernel<64, 2><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N,
-                                                                           wgs);
+    if (p.d == 64 && (p.Kl[0] << (p.lb - 4)) <= 32) { // two query blocks per wave (measured faster than one)
+        // workgroups of four waves (8 query blocks), four per CU: same occupancy as two of eight waves, cheaper barriers
+        // (measured 225 against 229 us)
+        const int64_t wgs = (int64_t)p.bh * (p.N / 128);
+        attn_fwd_shared_kernel<64, 2, 4><<<dim3((unsigned)wgs), 256, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N,
+                                                                              wgs);
     } else if (p.d == 64) {                           // K_0 > 32: both level-0 lists would not fit one register
         const int64_t wgs = (int64_t)p.bh * (p.N / 128);
         attn_fwd_shared_kernel<64, 1><<<dim3((unsigned)wgs), 512, 0, s>>>(t, (const uint16_t *)Q, (uint16_t *)O, LSE, p.N,
