@@ -3,11 +3,12 @@
 //
 // 256 consecutive queries (B = 16: the 16 fine query blocks under one level-1 query block) use the same lists at
 // every level >= 1 (Alg. 1, enrichment loop: block i reads row i / B^l of I^(l)), i.e. the same coarse key/value
-// tokens.  One workgroup of 8 waves owns such a group; every wave owns one or two of its 16-query tiles.
+// tokens.  One workgroup of 4 or 8 waves owns such a group or half of one; every wave owns one or two of its
+// 16-query tiles.
 //   Phase A (levels >= 1): the workgroup stages each tile of two 16-token blocks (K and V rows) once in
 //     LDS, double-buffered; every wave reads the K operand once and multiplies it with both of its query
 //     blocks, likewise the transposed V operand, so the gather traffic of the coarse tokens is paid once
-//     per 256 queries instead of once per 16.
+//     per 128 or 256 queries instead of once per 16.
 //   Phase B (level 0): each wave walks the level-0 tiles of each of its query tiles' lists; their K and V rows are
 //     fetched as whole cache lines and reach the operand layouts through the wave's private LDS tiles.
 // Score tiles are computed transposed (S^T = K Q^T) so that the accumulator layout (4 keys x 1 query per

@@ -87,7 +87,7 @@ bool select_top_fused(const Plan &p);
 
 // ---- bf16 MFMA kernels (B = 16 / 32 / 64, d = 64 or 128, N % 64 == 0) ----
 hipError_t launch_attn_fwd_mfma(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE, hipStream_t s);
-// variant that shares the coarse levels among the 16 sibling query blocks of a workgroup (d = 64, N % 256 == 0)
+// variant that shares the coarse levels among the 8 or 16 sibling query blocks of a workgroup (N % 256 == 0)
 hipError_t launch_attn_fwd_shared(const Plan &p, const LevelTable &t, const void *Q, void *O, float *LSE,
                                   hipStream_t s);
 // also writes D = rowsum(dO * O) for the key-major kernels that follow
