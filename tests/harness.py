@@ -22,7 +22,7 @@ import torch
 from oracle import llsa_oracle as orc
 from paper_2512_16615_amd import inputs, llsa
 
-BF16_ULP = 0.0          # no magnitude-scaled term: the plain bound holds on every shape tested (largest error seen 1.6e-2)
+BF16_ULP = 0.0          # no magnitude-scaled term: the plain bound holds on every shape tested (largest error seen 1.9e-2, on an edge case with a large softmax scale)
 TOL = {"f32": dict(out=1e-4, lse=1e-4, ulp=0.0), "bf16": dict(out=2e-2, lse=1e-3, ulp=BF16_ULP)}
 STATS: dict = {}        # output kind -> observed figures over every comparison of the session
 
