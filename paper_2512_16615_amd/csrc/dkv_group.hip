@@ -429,9 +429,9 @@ struct GatherArgs {
     int nblk, Kl, dense;
     int chain;                   // > 1: partials come from the chain kernel, which walked `chain` consecutive listers
 };
-template <int D>
-__global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
-    constexpr int U4 = GShape<D>::UNIT / 4, H4 = U4 / 2, PER = H4 / 256;   // float4 per partial / per half / per thread and half
+template <int D, int NT>
+__global__ void __launch_bounds__(NT) dkv_gather_kernel(GatherArgs a) {
+    constexpr int U4 = GShape<D>::UNIT / 4, H4 = U4 / 2, PER = H4 / NT;   // float4 per partial / per half / per thread and half
     const int tid = threadIdx.x;
     const int64_t bh = blockIdx.x / a.nkb, j = blockIdx.x % a.nkb;
     const f32x4 *part = reinterpret_cast<const f32x4 *>(a.part);
@@ -441,15 +441,15 @@ __global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
     if (a.dense) {
         const f32x4 *p = part + ((bh * a.cnt) * a.nblk + j) * U4;
 #pragma unroll
-        for (int x = 0; x < PER; ++x) { k[x] = p[tid + 256 * x]; v[x] = p[H4 + tid + 256 * x]; }
+        for (int x = 0; x < PER; ++x) { k[x] = p[tid + NT * x]; v[x] = p[H4 + tid + NT * x]; }
     } else {
         // first every thread resolves one lister (query block row and the position of j in that row's list),
-        // 256 at a time, then all threads add the partials in list order with independent loads
-        __shared__ int64_t unit[256];
+        // NT at a time, then all threads add the partials in list order with independent loads
+        __shared__ int64_t unit[NT];
         const int32_t beg = a.C[bh * (a.rows + 1) + j], end = a.C[bh * (a.rows + 1) + j + 1];
         const int32_t *lst = a.Iq + bh * a.rows * a.Kl;
-        for (int32_t e0 = beg; e0 < end; e0 += 256) {
-            const int32_t m = min(256, end - e0);
+        for (int32_t e0 = beg; e0 < end; e0 += NT) {
+            const int32_t m = min(NT, end - e0);
             __syncthreads();
             if (tid < m) {
                 const int64_t r = lst[e0 + tid];
@@ -470,13 +470,13 @@ __global__ void __launch_bounds__(256) dkv_gather_kernel(GatherArgs a) {
                 if (unit[e] < 0) continue;                                // same for every thread
                 const f32x4 *p = part + unit[e];
 #pragma unroll
-                for (int x = 0; x < PER; ++x) { k[x] += p[tid + 256 * x]; v[x] += p[H4 + tid + 256 * x]; }
+                for (int x = 0; x < PER; ++x) { k[x] += p[tid + NT * x]; v[x] += p[H4 + tid + NT * x]; }
             }
         }
     }
 #pragma unroll
     for (int x = 0; x < PER; ++x) {
-        const int e4 = tid + 256 * x;                                  // float4 index inside [16 keys][D channels]
+        const int e4 = tid + NT * x;                                   // float4 index inside [16 keys][D channels]
         const int64_t tok = j * 16 + e4 / (D / 4);
         if (tok >= a.n_l) continue;
         const int col = (e4 % (D / 4)) * 4;
@@ -611,8 +611,9 @@ static hipError_t finish_level(const Plan &p, const LevelTable &t, const GroupAr
     ga.nblk = a.nblk[l]; ga.Kl = dense ? 0 : p.Kl[l];
     ga.chain = l == 1 ? a.GC : 1;
     const dim3 grid((unsigned)(p.bh * ga.nkb));
-    if (p.d == 64) dkv_gather_kernel<64><<<grid, 256, 0, s>>>(ga);
-    else dkv_gather_kernel<128><<<grid, 256, 0, s>>>(ga);
+    // latency-bound (lists -> rows of I -> partials): more, smaller workgroups per CU shorten the launch
+    if (p.d == 64) dkv_gather_kernel<64, 128><<<grid, 128, 0, s>>>(ga);
+    else dkv_gather_kernel<128, 256><<<grid, 256, 0, s>>>(ga);
     return hipGetLastError();
 }
 
