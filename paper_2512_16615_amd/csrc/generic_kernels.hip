@@ -483,7 +483,8 @@ hipError_t launch_bwd_pre(const Plan &p, const void *O, const void *dO, float *D
 
 // -------------------------------------------------------------------------------- index transpose (Alg. 2)
 // count -> exclusive scan -> fill -> per-key ascending order.  Counting and filling use integer atomics;
-// the order they leave inside a key's list depends on timing, so a last pass sorts every list, which makes
+// the order they leave inside a key's list depends on timing, so a last pass sorts every list (an entry counts the
+// smaller ones of its list; lists of more than 4096 entries: a bitmap of the list's rows), which makes
 // the result (and with it the summation order of dK / dV) the same on every run.
 // All levels run in the same launches: blockIdx.y selects the level.
 struct CscLevel {
@@ -559,6 +560,9 @@ __global__ void csc_fill_kernel(CscLevels a) {
 }
 // one thread per list entry: its rank among the entries of the same key (entries are distinct query rows)
 // is its place in the key's ascending list.  The unsorted list is re-read through the caches.
+// Lists longer than kLongList are left to csc_sort_long_kernel (this pass costs len reads per entry).  A list is no
+// longer than the level has rows, so levels of up to kLongList rows (the headline's level 0 has 4096) need no second pass.
+constexpr int kLongList = 4096;
 __global__ void __launch_bounds__(256) csc_sort_kernel(CscLevels a) {
     const CscLevel &L = a.lv[blockIdx.y];
     const int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -566,13 +570,82 @@ __global__ void __launch_bounds__(256) csc_sort_kernel(CscLevels a) {
     const int64_t bh = e / L.eph, within = e % L.eph;
     const int32_t key = L.I[e], x = (int32_t)(within / L.Kl);
     const int32_t beg = L.C[bh * (L.T + 1) + key], end = L.C[bh * (L.T + 1) + key + 1];
+    if (end - beg > kLongList) return;
     const int32_t *src = L.Iq_tmp + bh * L.eph;
     int32_t rank = 0;
     for (int32_t b = beg; b < end; ++b) rank += (src[b] < x) ? 1 : 0;
     L.Iq[bh * L.eph + beg + rank] = x;
 }
+// Long lists: every lane of a wave looks at one key, and the wave then works through the long lists among its 64
+// keys together (usually none): the list's rows are marked in a bitmap of kSegRows rows at a time in LDS, and an
+// entry's place is the number of marked rows below it: one pass over the list per segment of rows instead of one
+// pass per entry, whatever the atomic fill's order was.  Keeps the transpose linear in the list length when many
+// queries pick the same key (constant keys: every row lists blocks 0 .. K-1).
+constexpr int kSegRows = 8192, kSegWords = kSegRows / 32;
+__global__ void __launch_bounds__(256) csc_sort_long_kernel(CscLevels a) {
+    __shared__ uint32_t bm_sh[4][kSegWords];
+    __shared__ int32_t pre_sh[4][kSegWords];
+    const CscLevel &L = a.lv[blockIdx.y];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t key0 = ((int64_t)blockIdx.x * 4 + wave) * 64;          // this wave's keys (over all heads)
+    if (key0 >= L.nk) return;
+    const int64_t mykey = min(key0 + lane, L.nk - 1);
+    const int32_t mybeg = L.C[(mykey / L.T) * (L.T + 1) + mykey % L.T];
+    const int32_t mylen = L.C[(mykey / L.T) * (L.T + 1) + mykey % L.T + 1] - mybeg;
+    uint64_t todo = __ballot(key0 + lane < L.nk && mylen > kLongList);
+    uint32_t *bm = bm_sh[wave];
+    int32_t *pre = pre_sh[wave];
+    while (todo) {
+        const int j = (int)__builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int64_t bh = (key0 + j) / L.T;
+        const int32_t beg = __shfl(mybeg, j, 64), len = __shfl(mylen, j, 64);
+        const int32_t *src = L.Iq_tmp + bh * L.eph + beg;
+        int32_t *dst = L.Iq + bh * L.eph + beg;
+        int32_t base = 0;                                   // entries in the segments done so far
+        for (int64_t s0 = 0; s0 < L.T; s0 += kSegRows) {
+            for (int w = lane; w < kSegWords; w += 64) bm[w] = 0u;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (int32_t e = lane; e < len; e += 64) {
+                const int64_t x = src[e] - s0;
+                if (x >= 0 && x < kSegRows) atomicOr(&bm[x >> 5], 1u << (x & 31));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            // marked rows below every word: lane holds kSegWords / 64 consecutive words
+            constexpr int PL = kSegWords / 64;
+            int32_t c[PL], mine = 0;
+#pragma unroll
+            for (int i = 0; i < PL; ++i) { c[i] = __popc(bm[PL * lane + i]); mine += c[i]; }
+            int32_t incl = mine;
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int32_t y = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += y;
+            }
+            int32_t run = incl - mine;
+#pragma unroll
+            for (int i = 0; i < PL; ++i) { pre[PL * lane + i] = run; run += c[i]; }
+            const int32_t total = __shfl(incl, 63, 64);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            for (int32_t e = lane; e < len; e += 64) {
+                const int32_t v = src[e];
+                const int64_t x = v - s0;
+                if (x >= 0 && x < kSegRows) {
+                    const int w = (int)(x >> 5);
+                    dst[base + pre[w] + __popc(bm[w] & ((1u << (x & 31)) - 1u))] = v;
+                }
+            }
+            base += total;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();                // the bitmap is cleared again only after these reads
+        }
+    }
+}
 
-// Alg. 2 for levels 0 .. top (the levels whose lists the backward uses), five launches in all
+// Alg. 2 for levels 0 .. top (the levels whose lists the backward uses), five launches in all (six for long levels)
 hipError_t launch_csc(const Plan &p, int top, const int32_t *indices, void *ws, hipStream_t s) {
     char *w = static_cast<char *>(ws);
     CscLevels a;
@@ -598,6 +671,8 @@ hipError_t launch_csc(const Plan &p, int top, const int32_t *indices, void *ws, 
     csc_scan_kernel<<<dim3(p.bh, nl), kScanThreads, 0, s>>>(a);
     csc_fill_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
     csc_sort_kernel<<<dim3((unsigned)((max_total + 255) / 256), nl), 256, 0, s>>>(a);
+    if (p.n[1] > kLongList)                                 // level 0 has the most rows; no list is longer than its level's rows
+        csc_sort_long_kernel<<<dim3((unsigned)((max_nk + 255) / 256), nl), 256, 0, s>>>(a);
     return hipGetLastError();
 }
 

@@ -276,3 +276,43 @@ def test_hip_graph_replays_match_eager(heads, N, L):
         torch.cuda.synchronize()
         for name, got, want in zip(("O", "LSE", "indices", "dQ", "dK", "dV"), (O, LSE, idx, dQ, dK, dV), ref):
             assert torch.equal(got, want), f"replay {rep}: {name} differs from the eager result"
+
+
+@pytest.mark.parametrize("N,heads", [(262144, 2), (1048576, 1)])
+def test_index_transpose_long_lists(N, heads):
+    """Alg. 2 on forced lists where many query blocks pick the same keys (what constant keys produce: every row lists
+    blocks 0 .. K-1): lists of up to 16384 and 65536 entries (two and eight row segments of the long-list pass), lists
+    just above and at the length where that pass takes over (4097 and 4096), and random rows; compared with the
+    oracle's transpose."""
+    cfg = dict(name="long_lists", batch=1, heads=heads, d=64, N=N, B=16, K=8, L=2, dtype="bf16", kind="smooth")
+    g = H.geometry(cfg)
+    plan = H.make_plan(cfg)
+    ws, idx = plan.alloc_workspace(True), plan.alloc_indices()
+    rng = np.random.default_rng(5)
+    T = g.n(1)
+    I = []
+    for h in range(heads):
+        r = np.sort(rng.integers(0, T, (T, 8), dtype=np.int64), axis=1).astype(np.int32)
+        bad = (r[:, 1:] == r[:, :-1]).any(axis=1)                                  # rows must hold distinct keys
+        r[bad] = np.arange(8, 16, dtype=np.int32)
+        if h == 0:
+            r[:] = np.arange(8, dtype=np.int32)                                    # every row lists keys 0 .. 7
+            r[: 4097, 7] = 100                                                     # key 100: 4097 listers
+            r[5000: 9096, 6] = 101                                                 # key 101: exactly 4096 listers
+        else:
+            r[::2, 0] = 0                                                          # key 0: at least every second row
+            r[::2] = np.sort(r[::2], axis=1)
+            bad = (r[:, 1:] == r[:, :-1]).any(axis=1)
+            r[bad] = np.arange(8, dtype=np.int32)
+        I.append(r)
+    I0 = np.stack(I)
+    plan.level_indices(idx, 0).copy_(torch.from_numpy(I0).cuda().view(1, heads, T, 8))
+    top = np.tile(np.arange(g.K_l(1), dtype=np.int32), (g.n(2), 1))               # level 1: any valid rows
+    plan.level_indices(idx, 1).copy_(torch.from_numpy(np.stack([top] * heads)).cuda().view(1, heads, g.n(2), g.K_l(1)))
+    llsa.index_transpose(plan, idx, ws)
+    torch.cuda.synchronize()
+    C, Iq = plan.csc_level(ws, 0)
+    for h in range(heads):
+        iq_ref, c_ref = orc.transpose(I0[h], T)
+        assert np.array_equal(C[h].cpu().numpy(), c_ref)
+        assert np.array_equal(Iq[h].cpu().numpy(), iq_ref)
