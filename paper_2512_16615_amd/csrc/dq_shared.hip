@@ -105,6 +105,18 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
     using B0 = std::integral_constant<int, 0>;
     using B1 = std::integral_constant<int, 1>;
 
+    // The level-0 lists of this wave's NB query blocks, fetched now so that phase B does not wait for them:
+    // lane (64 / NB) b + j holds the first token of 16-token tile j of query tile b's list (as in the forward kernel).
+    const int nb0 = t.bseg[1];
+    int tok0 = 0;
+    {
+        const int b = lane / (64 / NB), j = lane % (64 / NB);
+        if (j < nb0) {
+            const int64_t row = (blk0 + NB * wave + b) >> t.ls;
+            tok0 = (t.I[0][(bh * t.rows[0] + row) * t.Kl[0] + (j >> t.ls)] << t.lb) + ((j & ((1 << t.ls) - 1)) << 4);
+        }
+    }
+
     // ------------------------------------------------------------------ phase A: shared coarse levels
     const int c_begin = t.nlev > 1 ? t.bseg[1] : t.bseg[t.nlev];
     const int nbc = t.bseg[t.nlev] - c_begin;
@@ -196,29 +208,26 @@ dq_shared_kernel(LevelTable t, const uint16_t *__restrict__ Q, const uint16_t *_
     // the MFMA operand layout straight from memory, 16 rows x half a line per instruction, caps the gather rate at a
     // third of what the L2 delivers) and reach the operand layouts through the wave's own LDS tiles.
     __syncthreads();                                                  // phase A's buffers are free
-    const int nb0 = t.bseg[1];
     char *my = lds + wave * (TILE + VTILE), *my_v = my + TILE;
+    const char *K0 = static_cast<const char *>(t.K[0]), *V0 = static_cast<const char *>(t.V[0]);
     unsigned voff[VCH];
 #pragma unroll
     for (int u = 0; u < VCH; ++u) voff[u] = (unsigned)((((lane / PARTS + KPU * u) & 15) * D + (lane % PARTS) * 8) * 2);
 
     auto phase_b = [&](auto bsel) {
         constexpr int b = decltype(bsel)::value;
-        BlockTable tab;
-        tab.fill(t, bh, blk0 + NB * wave + b, 0, 0, lane, D, 1);      // level 0 only
         u32x4 kreg[VCH], vreg[VCH];
         auto load_tile = [&](int j0) {
-            const char *kp[2], *vp[2];
+            int64_t off[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int j = (j0 + h < nb0) ? j0 + h : j0;
-                kp[h] = tab.K(j);
-                vp[h] = tab.V(j);
+                const int j = (j0 + h < nb0) ? j0 + h : j0;           // an absent second half re-reads the first
+                off[h] = (bh * N + __builtin_amdgcn_readlane(tok0, (64 / NB) * b + j)) * (D * 2);
             }
 #pragma unroll
             for (int u = 0; u < VCH; ++u) {
-                kreg[u] = gload16b(kp[(KPU * u) >> 4], voff[u]);
-                vreg[u] = gload16b(vp[(KPU * u) >> 4], voff[u]);
+                kreg[u] = gload16b(K0 + off[(KPU * u) >> 4], voff[u]);
+                vreg[u] = gload16b(V0 + off[(KPU * u) >> 4], voff[u]);
             }
         };
         load_tile(0);
