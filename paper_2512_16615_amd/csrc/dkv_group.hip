@@ -75,7 +75,7 @@ __device__ __forceinline__ void stage_load(StageRegs<D, NTHR> &r, const GroupArg
         r.s[k] = i < 256 ? a.LSE[row0 + i] : a.Dsum[row0 + i - 256];
     }
 }
-// ... and from there into LDS (qs, gs: swizzled rows; st: LSE [256] | D [256])
+// ... and from there into LDS (qs, gs: swizzled rows; st: -LSE log2(e) [256] | D [256])
 template <int D, int NTHR>
 __device__ __forceinline__ void stage_store(const StageRegs<D, NTHR> &r, char *qs, char *gs, float *st, int tid) {
     constexpr int CH = GShape<D>::CH;
@@ -85,11 +85,14 @@ __device__ __forceinline__ void stage_store(const StageRegs<D, NTHR> &r, char *q
         *reinterpret_cast<u32x4 *>(qs + swz<D>(cc / CH, cc % CH)) = r.q[k];
         *reinterpret_cast<u32x4 *>(gs + swz<D>(cc / CH, cc % CH)) = r.g[k];
     }
+    // LSE goes in as -LSE log2(e), the form the tiles' exponentials take it in
 #pragma unroll
-    for (int k = 0; k < 512 / NTHR; ++k) st[tid + NTHR * k] = r.s[k];
+    for (int k = 0; k < 512 / NTHR; ++k) st[tid + NTHR * k] = (tid + NTHR * k < 256) ? r.s[k] * -kLog2e : r.s[k];
 }
 
 // One key block held by a wave: its K / V rows as B operands, the level's log2 weight, its gradient sums.
+// The tiles compute P = exp(z - LSE) without the level's weight B^l (a power of two for the block sizes of this
+// path: scaling by it commutes with the bf16 rounding of P and dS); the sums take it when they are written.
 template <int D> struct BlockAcc {
     bf16x8 kop[D / 32], vop[D / 32];
     float bias2;
@@ -140,7 +143,7 @@ __device__ __forceinline__ void group_tile(const char *qs, const char *gs, const
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[b][h][r], sc2, fmaf(l2[r], -kLog2e, blk[b].bias2)));
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[b][h][r], sc2, l2[r]));   // without the level's weight
                 s[b][h][r] = p;
                 dp[b][h][r] = p * (dp[b][h][r] - dl[r]);
             }
@@ -174,13 +177,15 @@ __device__ __forceinline__ float *partial_ptr(const LevelTable &t, const GroupAr
 
 template <int D> __device__ __forceinline__ void store_partial(float *dst, const BlockAcc<D> &b, float scale, int lane) {
     dst += (lane & 15) * D + 4 * (lane >> 4);
+    const float w = __builtin_amdgcn_exp2f(b.bias2);        // the level's weight, left out of the tiles' P
+    const float ws = w * scale;
 #pragma unroll
     for (int n = 0; n < D / 16; ++n) {
-        f32x4 k = b.accK[n];
+        f32x4 k = b.accK[n], v = b.accV[n];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) k[r] *= scale;
+        for (int r = 0; r < 4; ++r) { k[r] *= ws; v[r] *= w; }
         *reinterpret_cast<f32x4 *>(dst + n * 16) = k;
-        *reinterpret_cast<f32x4 *>(dst + 16 * D + n * 16) = b.accV[n];
+        *reinterpret_cast<f32x4 *>(dst + 16 * D + n * 16) = v;
     }
 }
 
@@ -396,9 +401,9 @@ __global__ void __launch_bounds__(512) dkv_upper_kernel(LevelTable t, GroupArgs 
                     for (int c = 0; c < 4; ++c) sum[c] += x[c];
                 }
                 const bool isV = slot >= S::NT;
-                if (!isV)
+                const float w = __builtin_amdgcn_exp2f(dn[0].bias2) * (isV ? 1.f : a.scale);   // level weight (and scale for dK)
 #pragma unroll
-                    for (int c = 0; c < 4; ++c) sum[c] *= a.scale;
+                for (int c = 0; c < 4; ++c) sum[c] *= w;
                 *reinterpret_cast<f32x4 *>(dst + (isV ? 16 * D : 0) + (isV ? slot - S::NT : slot) * 16) = sum;
             }
         }
