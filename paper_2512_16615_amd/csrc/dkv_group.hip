@@ -528,18 +528,14 @@ static int upper_G(const Plan &p) {
 
 // Level-1 query blocks one workgroup of the chain kernel walks (1: the plain group kernel takes level 1).
 // d = 64 with rows of 8 level-1 blocks, level 1 sparse and the only level the kernel is given.
-#ifndef LLSA_CHAIN
-#define LLSA_CHAIN 8
-#endif
-#ifndef LLSA_CHAIN_WG
-#define LLSA_CHAIN_WG 512
-#endif
+// Measured at the headline: 8 query blocks per workgroup in 512 workgroups (two per CU) 259 us for the coarse stage,
+// 4 in 1024: 275 us, 2: 297 us, 16 in 256 workgroups: 286 us, one query block per workgroup (no carrying): 357 us.
 static int chain_len(const Plan &p) {
     if (p.d != 64 || p.L < 2 || p.Kl[1] != 8) return 1;
     if (upper_G(p) == 0 && dkv_group_top(p) > 1) return 1;
     const int64_t NR = p.N / 256;
-    int GC = LLSA_CHAIN;
-    while (GC > 1 && (NR % GC != 0 || (int64_t)p.bh * (NR / GC) < LLSA_CHAIN_WG)) GC >>= 1;   // two workgroups per CU
+    int GC = 8;
+    while (GC > 1 && (NR % GC != 0 || (int64_t)p.bh * (NR / GC) < 512)) GC >>= 1;   // at least two workgroups per CU
     return GC;
 }
 
